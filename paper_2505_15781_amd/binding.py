@@ -1,0 +1,259 @@
+"""ctypes binding of libdkv.so: argument marshalling only, every step runs in the HIP kernels.
+
+PyTorch supplies device memory and the stream. The library must have been built
+(`python -m paper_2505_15781_amd.build`); importing this module without it raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdkv.so")
+BF16, FP32 = 0, 1
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_15781_amd.build` "
+                      "(there is no CPU fallback)")
+lib = C.CDLL(LIB_PATH)
+
+c_i32, c_f32, c_vp, c_sz = C.c_int32, C.c_float, C.c_void_p, C.c_size_t
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [(n, c_i32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn",
+                                     "vocab", "mask_id", "dtype")] + [("rms_eps", c_f32), ("rope_theta", c_f32)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("embed", c_vp), ("lm_head", c_vp), ("final_norm", c_vp)] + \
+               [(n, C.POINTER(c_vp)) for n in ("wqkv", "wo", "w_gate_up", "w_down", "norm1", "norm2")]
+
+
+class RunDesc(C.Structure):
+    _fields_ = [(n, c_i32) for n in ("batch", "prompt_len", "gen_len", "steps", "block_len", "refresh_interval",
+                                     "variant", "delay", "window", "window_center", "include_prev", "remask")] + \
+               [("order", c_vp)]
+
+
+class Buffers(C.Structure):
+    _fields_ = [(n, c_vp) for n in ("k_cache", "v_cache", "tokens", "masked", "stamp", "decoded_pos",
+                                    "decoded_tok", "decoded_conf", "workspace")] + [("workspace_bytes", c_sz)]
+
+
+lib.dkv_last_error.restype = C.c_char_p
+lib.dkv_workspace_bytes.restype = c_sz
+lib.dkv_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(RunDesc)]
+lib.dkv_init_cache.argtypes = [C.POINTER(c_vp), C.POINTER(ModelDesc), C.POINTER(Weights), C.POINTER(RunDesc),
+                               C.POINTER(Buffers), c_vp]
+lib.dkv_select_active.argtypes = [c_vp, c_i32, c_vp, c_vp, C.POINTER(c_i32)]
+lib.dkv_denoise_step.argtypes = [c_vp, c_i32, c_vp, c_vp, c_vp]
+lib.dkv_refresh.argtypes = [c_vp, c_i32]
+lib.dkv_read_rows.argtypes = [c_vp, c_vp, c_vp, c_i32, C.POINTER(c_i32)]
+lib.dkv_read_candidates.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, C.POINTER(c_i32)]
+lib.dkv_read_hidden.argtypes = [c_vp, c_vp, c_i32, C.POINTER(c_i32)]
+lib.dkv_destroy.argtypes = [c_vp]
+lib.dkv_attn_update_workspace_bytes.restype = c_sz
+lib.dkv_attn_update_workspace_bytes.argtypes = [c_i32] * 7
+lib.dkv_attn_update.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp, c_sz, c_vp]
+lib.dkv_gemm_workspace_bytes.restype = c_sz
+lib.dkv_gemm_workspace_bytes.argtypes = [c_i32] * 4
+lib.dkv_gemm.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_sz, c_vp]
+
+
+class DkvError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"dkv error {code}: {text}")
+        self.code = code
+
+
+def last_error():
+    return lib.dkv_last_error().decode()
+
+
+def _check(rc):
+    if rc != 0:
+        raise DkvError(rc, last_error())
+
+
+def _ptr(t):
+    return None if t is None else c_vp(t.data_ptr())
+
+
+def _stream():
+    return c_vp(torch.cuda.current_stream().cuda_stream)
+
+
+def _tdtype(dtype):
+    return torch.bfloat16 if dtype == BF16 else torch.float32
+
+
+def model_desc(m):
+    return ModelDesc(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn, m.vocab, m.mask_id,
+                     m.dtype, m.rms_eps, m.rope_theta)
+
+
+def run_desc(r, order_ptr=None):
+    return RunDesc(r.batch, r.prompt_len, r.gen_len, r.steps, r.block_len, r.refresh_interval, r.variant, r.delay,
+                   r.window, r.window_center, r.include_prev, r.remask, order_ptr)
+
+
+def upload_weights(model, synth, device="cuda", layers=None):
+    """Device tensors in the layouts the library documents, from a dkv_inputs.SynthWeights."""
+    td = _tdtype(model.dtype)
+
+    def dev(x, dt=td):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(device=device, dtype=dt)
+
+    out = {"embed": dev(synth.embed()), "lm_head": dev(synth.lm_head()),
+           "final_norm": dev(synth.final_norm(), torch.float32),
+           "wqkv": [], "wo": [], "w_gate_up": [], "w_down": [], "norm1": [], "norm2": []}
+    for l in (range(model.n_layers) if layers is None else layers):
+        w = synth.layer(l)
+        out["wqkv"].append(dev(np.concatenate([w["wq"], w["wk"], w["wv"]], axis=0)))
+        out["wo"].append(dev(w["wo"]))
+        gu = np.stack([w["w_gate"], w["w_up"]], axis=1).reshape(2 * model.d_ffn, model.d_model)
+        out["w_gate_up"].append(dev(gu))
+        out["w_down"].append(dev(w["w_down"]))
+        out["norm1"].append(dev(w["norm1"], torch.float32))
+        out["norm2"].append(dev(w["norm2"], torch.float32))
+    return out
+
+
+def random_weights(model, seed, device="cuda"):
+    """Device-side N(0, 0.02) weights of the documented shapes (for throughput runs)."""
+    g = torch.Generator(device=device).manual_seed(seed)
+    td = _tdtype(model.dtype)
+
+    def mat(r, c):
+        return (torch.randn(r, c, generator=g, device=device, dtype=torch.float32) * 0.02).to(td)
+
+    def gain():
+        return 1.0 + 0.1 * torch.randn(model.d_model, generator=g, device=device, dtype=torch.float32)
+
+    m = model
+    out = {"embed": mat(m.vocab, m.d_model), "lm_head": mat(m.vocab, m.d_model), "final_norm": gain(),
+           "wqkv": [], "wo": [], "w_gate_up": [], "w_down": [], "norm1": [], "norm2": []}
+    for _ in range(m.n_layers):
+        out["wqkv"].append(mat(m.qkv_rows, m.d_model))
+        out["wo"].append(mat(m.d_model, m.n_q_heads * m.head_dim))
+        out["w_gate_up"].append(mat(2 * m.d_ffn, m.d_model))
+        out["w_down"].append(mat(m.d_model, m.d_ffn))
+        out["norm1"].append(gain())
+        out["norm2"].append(gain())
+    return out
+
+
+class DkvRun:
+    """One generation run: owns the device buffers (torch tensors) and the library context."""
+
+    def __init__(self, model, run, weights, prompt, order=None, device="cuda"):
+        self.model, self.run, self.w = model, run, weights
+        B, L = run.batch, run.seq_len
+        self.k = run.k_per_step
+        td = _tdtype(model.dtype)
+        self.md = model_desc(model)
+        self.order = None if order is None else torch.as_tensor(np.asarray(order), dtype=torch.int32, device=device).contiguous()
+        self.rd = run_desc(run, _ptr(self.order))
+        ws_bytes = lib.dkv_workspace_bytes(C.byref(self.md), C.byref(self.rd))
+        if ws_bytes == 0:
+            raise DkvError(-1, "descriptors rejected by dkv_workspace_bytes")
+        cache_shape = (model.n_layers, B, model.n_kv_heads, L, model.head_dim)
+        self.k_cache = torch.empty(cache_shape, dtype=td, device=device)
+        self.v_cache = torch.empty(cache_shape, dtype=td, device=device)
+        self.tokens = torch.zeros((B, L), dtype=torch.int32, device=device)
+        self.tokens[:, :run.prompt_len] = torch.as_tensor(np.asarray(prompt), dtype=torch.int32, device=device)
+        self.masked = torch.empty((B, L), dtype=torch.uint8, device=device)
+        self.stamp = torch.empty((B, L), dtype=torch.int32, device=device)
+        self.decoded_pos = torch.empty((run.steps, B, self.k), dtype=torch.int32, device=device)
+        self.decoded_tok = torch.empty((run.steps, B, self.k), dtype=torch.int32, device=device)
+        self.decoded_conf = torch.empty((run.steps, B, self.k), dtype=torch.float32, device=device)
+        self.workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=device)
+        ws_ptr = (self.workspace.data_ptr() + 255) // 256 * 256
+        self._arrs = {}
+        wd = Weights(_ptr(weights["embed"]), _ptr(weights["lm_head"]), _ptr(weights["final_norm"]))
+        for name in ("wqkv", "wo", "w_gate_up", "w_down", "norm1", "norm2"):
+            arr = (c_vp * model.n_layers)(*[t.data_ptr() for t in weights[name]])
+            self._arrs[name] = arr
+            setattr(wd, name, arr)
+        bd = Buffers(_ptr(self.k_cache), _ptr(self.v_cache), _ptr(self.tokens), _ptr(self.masked), _ptr(self.stamp),
+                     _ptr(self.decoded_pos), _ptr(self.decoded_tok), _ptr(self.decoded_conf), c_vp(ws_ptr), ws_bytes)
+        self.ctx = c_vp()
+        _check(lib.dkv_init_cache(C.byref(self.ctx), C.byref(self.md), C.byref(wd), C.byref(self.rd), C.byref(bd),
+                                  _stream()))
+        self.workspace_bytes = ws_bytes
+
+    def select_active(self, step, active_idx=None, active_off=None):
+        ub = c_i32(0)
+        _check(lib.dkv_select_active(self.ctx, step, _ptr(active_idx), _ptr(active_off), C.byref(ub)))
+        return ub.value
+
+    def denoise_step(self, step, forced_pos=None, forced_tok=None, logits_out=None):
+        _check(lib.dkv_denoise_step(self.ctx, step, _ptr(forced_pos), _ptr(forced_tok), _ptr(logits_out)))
+
+    def refresh(self, scope):
+        _check(lib.dkv_refresh(self.ctx, scope))
+
+    def read_rows(self):
+        cap = self.run.batch * self.run.seq_len
+        pos = np.empty(cap, dtype=np.int32)
+        off = np.empty(self.run.batch + 1, dtype=np.int32)
+        n = c_i32(0)
+        _check(lib.dkv_read_rows(self.ctx, pos.ctypes.data, off.ctypes.data, cap, C.byref(n)))
+        return pos[:n.value].copy(), off
+
+    def read_candidates(self):
+        cap = self.run.batch * self.run.block_len
+        pos = np.empty(cap, dtype=np.int32)
+        tok = np.empty(cap, dtype=np.int32)
+        conf = np.empty(cap, dtype=np.float32)
+        off = np.empty(self.run.batch + 1, dtype=np.int32)
+        n = c_i32(0)
+        _check(lib.dkv_read_candidates(self.ctx, pos.ctypes.data, tok.ctypes.data, conf.ctypes.data,
+                                       off.ctypes.data, cap, C.byref(n)))
+        return pos[:n.value].copy(), tok[:n.value].copy(), conf[:n.value].copy(), off
+
+    def read_hidden(self):
+        cap = self.run.batch * self.run.seq_len
+        out = np.empty((cap, self.model.d_model), dtype=np.float32)
+        n = c_i32(0)
+        _check(lib.dkv_read_hidden(self.ctx, out.ctypes.data, cap, C.byref(n)))
+        return out[:n.value].copy()
+
+    def close(self):
+        if self.ctx:
+            lib.dkv_destroy(self.ctx)
+            self.ctx = c_vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def attn_update_workspace_bytes(batch, n_q_heads, n_kv_heads, seq_len, head_dim, dtype, max_rows_per_seq):
+    return lib.dkv_attn_update_workspace_bytes(batch, n_q_heads, n_kv_heads, seq_len, head_dim, dtype,
+                                               max_rows_per_seq)
+
+
+def attn_update(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, rows, max_rows_per_seq, dtype,
+                workspace):
+    B, Hkv, L, dh = k_cache.shape
+    Hq = q.shape[1] if q is not None and q.dim() == 3 else out.shape[1]
+    _check(lib.dkv_attn_update(_ptr(k_cache), _ptr(v_cache), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(active_idx),
+                               _ptr(active_off), _ptr(out), rows, max_rows_per_seq, B, Hq, Hkv, L, dh, dtype,
+                               _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                               _stream()))
+
+
+def gemm(x, w, dtype):
+    """y = x @ w.T in fp32 through the library's projection kernel."""
+    m, k = x.shape
+    n = w.shape[0]
+    y = torch.empty((m, n), dtype=torch.float32, device=x.device)
+    nb = lib.dkv_gemm_workspace_bytes(m, n, k, dtype)
+    ws = torch.empty(max(nb, 4), dtype=torch.uint8, device=x.device)
+    _check(lib.dkv_gemm(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, _ptr(ws), nb, _stream()))
+    return y

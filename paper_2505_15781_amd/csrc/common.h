@@ -1,0 +1,105 @@
+// Shared device/host helpers of the dKV-Cache HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/dkv.h"
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+#define DKV_WAVE 64
+
+void dkv_set_error(const char *fmt, ...);
+
+#define DKV_HIP_TRY(expr)                                                                  \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess) {                                                            \
+            dkv_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, \
+                          __LINE__);                                                       \
+            return DKV_E_HIP;                                                              \
+        }                                                                                  \
+    } while (0)
+
+#define DKV_LAUNCH_CHECK()  DKV_HIP_TRY(hipGetLastError())
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct El;
+template <> struct El<float> {
+    static __device__ __forceinline__ float ld(const float *p) { return *p; }
+    static __device__ __forceinline__ void st(float *p, float v) { *p = v; }
+};
+template <> struct El<bf16_t> {
+    static __device__ __forceinline__ float ld(const bf16_t *p) { return bf2f(*p); }
+    static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f2bf(v); }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Block-wide sum for blocks of up to 1024 threads (a multiple of 64); `red` holds >= 16 floats.
+__device__ __forceinline__ float block_sum(float v, float *red) {
+    v = wave_sum(v);
+    int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int i = 0; i < nw; ++i) t += red[i];
+    return t;
+}
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ---- internal launchers (host side) --------------------------------------------------------
+
+// Plan of one projection: tile shape and split of the K dimension.
+struct GemmPlan {
+    int bm;        // rows per workgroup tile
+    int split_k;   // number of K slices; slice s writes partial[s]
+};
+GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k);
+
+// partial[s][m][n] (fp32, stride m_cap rows per slice) = A[m, k-slice] * W[n, k-slice]^T.
+// Rows >= *m_dev (when m_dev != nullptr) are neither read nor written.
+int dkv_launch_gemm(int dtype, const void *A, const void *W, float *partial, int m_upper, int m_cap,
+                    const int *m_dev, int n, int k, GemmPlan plan, hipStream_t stream);
+
+struct AttnPlan {
+    int use_mfma;     // 1: bf16 MFMA kernel, 0: generic kernel
+    int q_tiles;      // 16-row query tiles per (sequence, kv head), upper bound
+    int splits;       // slices of the key range
+    int tiles_per_split;
+};
+AttnPlan dkv_attn_plan(int dtype, int batch, int n_q_heads, int n_kv_heads, int seq_len, int head_dim,
+                       int max_rows_per_seq);
+size_t dkv_attn_partial_bytes(const AttnPlan &p, int batch, int n_q_heads, int n_kv_heads, int head_dim);
+
+// out[r, h, :] = attention of q[r, h] over all seq_len positions of sequence b(r).
+int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const void *v_cache,
+                         const int *row_off, void *out, int batch, int n_q_heads, int n_kv_heads,
+                         int seq_len, int head_dim, int rows_upper, AttnPlan plan, void *partial,
+                         hipStream_t stream);

@@ -1,0 +1,573 @@
+// Row-wise and index kernels of one denoising step: active-set selection, embedding gather, RMSNorm,
+// rotary embedding + K/V scatter into the position-indexed cache, SwiGLU, vocabulary softmax
+// statistics, and the confidence top-k commit.
+#include "rowops.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------------
+// Active set (Eq. 4; Sec. 3.3 refresh / Prefill / PD; Sec. 3.4 Greedy). One workgroup walks the
+// sequences in order and compacts the flagged positions with a block-wide prefix sum, so rows come
+// out sequence by sequence, position ascending.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int block_excl_scan(int v, int *wave_tot, int *total) {
+    // exclusive prefix sum over the block (1024 threads); returns the prefix, *total the sum
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int y = __shfl_up(x, o, 64);
+        if (lane >= o) x += y;
+    }
+    __syncthreads();
+    if (lane == 63) wave_tot[w] = x;
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int i = 0; i < nw; ++i) {
+        int t = wave_tot[i];
+        if (i < w) base += t;
+        tot += t;
+    }
+    *total = tot;
+    return base + x - v;
+}
+
+__global__ __launch_bounds__(1024) void select_active_kernel(SelectArgs a) {
+    __shared__ int wave_tot[16];
+    int row_base = 0, cand_base = 0;
+    for (int b = 0; b < a.batch; ++b) {
+        if (threadIdx.x == 0) {
+            a.row_off[b] = row_base;
+            a.cand_off[b] = cand_base;
+        }
+        const uint8_t *mk = a.masked + (size_t)b * a.L;
+        for (int p0 = 0; p0 < a.L; p0 += blockDim.x) {
+            const int p = p0 + threadIdx.x;
+            int act = 0, cand = 0;
+            if (p < a.L) {
+                const bool m = mk[p] != 0;
+                if (a.mode == SEL_ALL) act = 1;
+                else if (a.mode == SEL_GEN) act = p >= a.P;
+                else if (a.mode == SEL_MASKED_PREV) {
+                    act = m;
+                    if (!act && a.use_prev)
+                        for (int j = 0; j < a.k; ++j) act |= (a.d_prev[b * a.k + j] == p);
+                } else {   // SEL_GREEDY
+                    for (int j = 0; j < a.k; ++j) {
+                        const int cur = a.order[(size_t)b * a.G + a.step * a.k + j];
+                        const int prev = a.d_prev[b * a.k + j];
+                        act |= (cur == p);
+                        if (a.use_prev) act |= (prev == p);
+                        const int c = a.center_prev ? prev : cur;
+                        if (a.window > 0 && c >= 0) act |= (p >= c - a.win_lo && p <= c + a.win_hi);
+                    }
+                }
+                cand = act && m && p >= a.blk_lo && p < a.blk_hi;
+            }
+            int tot_a, tot_c;
+            const int ia = block_excl_scan(act, wave_tot, &tot_a);
+            const int ic = block_excl_scan(cand, wave_tot, &tot_c);
+            if (act) {
+                a.row_pos[row_base + ia] = p;
+                a.row_seq[row_base + ia] = b;
+            }
+            if (cand) {
+                a.cand_row[cand_base + ic] = row_base + ia;
+                a.cand_pos[cand_base + ic] = p;
+            }
+            row_base += tot_a;
+            cand_base += tot_c;
+        }
+    }
+    if (threadIdx.x == 0) {
+        a.row_off[a.batch] = row_base;
+        a.cand_off[a.batch] = cand_base;
+        a.counts[0] = row_base;
+        a.counts[1] = cand_base;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// h[r] = embed[token at (seq, pos)], a[r] = RMSNorm(h[r]) * gain; stamps the row's position.
+// ------------------------------------------------------------------------------------------------
+template <typename T, int VPT>
+__global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ embed,
+                                                         const int *__restrict__ tokens,
+                                                         const int *__restrict__ row_pos,
+                                                         const int *__restrict__ row_seq,
+                                                         const int *__restrict__ counts,
+                                                         const float *__restrict__ gain, float *__restrict__ h,
+                                                         T *__restrict__ a, int *__restrict__ stamp, int L,
+                                                         int d, float eps, int step) {
+    __shared__ float red[16];
+    const int r = blockIdx.x;
+    if (r >= counts[0]) return;
+    const int b = row_seq[r], p = row_pos[r];
+    const int tok = tokens[(size_t)b * L + p];
+    if (threadIdx.x == 0) stamp[(size_t)b * L + p] = step;
+    const T *e = embed + (size_t)tok * d;
+    float v[VPT], ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        int c = threadIdx.x + 256 * i;
+        v[i] = c < d ? El<T>::ld(e + c) : 0.f;
+        ss += v[i] * v[i];
+    }
+    ss = block_sum(ss, red);
+    const float rs = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        int c = threadIdx.x + 256 * i;
+        if (c < d) {
+            h[(size_t)r * d + c] = v[i];
+            El<T>::st(a + (size_t)r * d + c, v[i] * rs * gain[c]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// h[r] += sum_s partial[s][r]; a[r] = RMSNorm(h[r]) * gain (the next projection's input).
+// ------------------------------------------------------------------------------------------------
+template <typename T, int VPT>
+__global__ __launch_bounds__(256) void residual_norm_kernel(const float *__restrict__ part, int splits,
+                                                            size_t split_stride,
+                                                            const int *__restrict__ counts,
+                                                            const float *__restrict__ gain,
+                                                            float *__restrict__ h, T *__restrict__ a, int d,
+                                                            float eps) {
+    __shared__ float red[16];
+    const int r = blockIdx.x;
+    if (r >= counts[0]) return;
+    float v[VPT], ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        int c = threadIdx.x + 256 * i;
+        float x = 0.f;
+        if (c < d) {
+            x = h[(size_t)r * d + c];
+            for (int s = 0; s < splits; ++s) x += part[s * split_stride + (size_t)r * d + c];
+        }
+        v[i] = x;
+        ss += x * x;
+    }
+    ss = block_sum(ss, red);
+    const float rs = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        int c = threadIdx.x + 256 * i;
+        if (c < d) {
+            h[(size_t)r * d + c] = v[i];
+            El<T>::st(a + (size_t)r * d + c, v[i] * rs * gain[c]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Rotary embedding of q and k with the row's true position (Appendix A: positional embeddings follow
+// the token), q to its row buffer, k and v to the cache rows of that position (Algorithm 1 line 4,
+// position-indexed instead of concatenated).
+// qkv partials: [splits][rows][(Hq + 2 Hkv) * dh] fp32. rope: [L][dh/2] (cos, sin).
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rope_scatter_kernel(const float *__restrict__ part, int splits,
+                                                           size_t split_stride,
+                                                           const int *__restrict__ row_pos,
+                                                           const int *__restrict__ row_seq,
+                                                           const int *__restrict__ counts,
+                                                           const float2 *__restrict__ rope, T *__restrict__ q,
+                                                           T *__restrict__ Kc, T *__restrict__ Vc, int Hq,
+                                                           int Hkv, int dh, int L) {
+    const int r = blockIdx.x;
+    if (r >= counts[0]) return;
+    const int b = row_seq[r], p = row_pos[r];
+    const int half = dh >> 1, slots = Hq + 2 * Hkv, n = slots * dh;
+    const float *src = part + (size_t)r * n;
+    for (int e = threadIdx.x; e < slots * half; e += 256) {
+        const int hs = e / half, i = e % half;
+        float x1 = 0.f, x2 = 0.f;
+        for (int s = 0; s < splits; ++s) {
+            x1 += src[s * split_stride + hs * dh + i];
+            x2 += src[s * split_stride + hs * dh + i + half];
+        }
+        if (hs < Hq + Hkv) {
+            const float2 cs = rope[(size_t)p * half + i];
+            const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
+            x1 = y1;
+            x2 = y2;
+        }
+        T *dst;
+        if (hs < Hq) dst = q + ((size_t)r * Hq + hs) * dh;
+        else if (hs < Hq + Hkv) dst = Kc + (((size_t)b * Hkv + (hs - Hq)) * L + p) * dh;
+        else dst = Vc + (((size_t)b * Hkv + (hs - Hq - Hkv)) * L + p) * dh;
+        El<T>::st(dst + i, x1);
+        El<T>::st(dst + i + half, x2);
+    }
+}
+
+// f[r][j] = silu(gate_j) * up_j with gate/up interleaved in the projection output.
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ part, int splits,
+                                                     size_t split_stride, const int *__restrict__ counts,
+                                                     T *__restrict__ f, int F, int fast_exp) {
+    const int r = blockIdx.y;
+    if (r >= counts[0]) return;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= F) return;
+    const float2 *src = reinterpret_cast<const float2 *>(part + (size_t)r * 2 * F) + j;
+    float g = 0.f, u = 0.f;
+    for (int s = 0; s < splits; ++s) {
+        float2 v = *reinterpret_cast<const float2 *>(reinterpret_cast<const float *>(src) + s * split_stride);
+        g += v.x;
+        u += v.y;
+    }
+    const float sg = g / (1.0f + (fast_exp ? __expf(-g) : expf(-g)));
+    El<T>::st(f + (size_t)r * F + j, sg * u);
+}
+
+// dst[c] = src[cand_row[c]] (the rows that go through the vocabulary projection)
+template <typename T>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const T *__restrict__ src,
+                                                          const int *__restrict__ cand_row,
+                                                          const int *__restrict__ counts, T *__restrict__ dst,
+                                                          int d) {
+    const int c = blockIdx.x;
+    if (c >= counts[1]) return;
+    const T *s = src + (size_t)cand_row[c] * d;
+    for (int i = threadIdx.x; i < d; i += 256) dst[(size_t)c * d + i] = s[i];
+}
+
+// out[m][n] = sum_s part[s][m][n]
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int splits,
+                                                              size_t split_stride, float *__restrict__ out,
+                                                              size_t total) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    float v = 0.f;
+    for (int s = 0; s < splits; ++s) v += part[s * split_stride + i];
+    out[i] = v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Per candidate row: token = arg max of the logits with MASK excluded (lowest id on ties),
+// confidence = its softmax probability (Sec. 3.1: keep the most confident predictions).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void head_stats_kernel(const float *__restrict__ logits,
+                                                          const int *__restrict__ counts, int V, int mask_id,
+                                                          int *__restrict__ tok, float *__restrict__ conf,
+                                                          int *__restrict__ status) {
+    __shared__ float smax[16];
+    __shared__ int sidx[16];
+    __shared__ float red[16];
+    const int c = blockIdx.x;
+    if (c >= counts[1]) return;
+    const float *row = logits + (size_t)c * V;
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    bool nan = false;
+    for (int v = threadIdx.x; v < V; v += blockDim.x) {
+        if (v == mask_id) continue;
+        float x = row[v];
+        nan |= (x != x);
+        if (x > best) { best = x; bi = v; }      // ascending v per thread: first max wins
+    }
+    // wave then block reduction of (value, lowest index)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float ob = __shfl_xor(best, o, 64);
+        int oi = __shfl_xor(bi, o, 64);
+        if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
+    }
+    const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if ((threadIdx.x & 63) == 0) { smax[w] = best; sidx[w] = bi; }
+    if (__syncthreads_or(nan) && threadIdx.x == 0) atomicOr(status, STATUS_NAN);
+    best = smax[0]; bi = sidx[0];
+    for (int i = 1; i < nw; ++i)
+        if (smax[i] > best || (smax[i] == best && sidx[i] < bi)) { best = smax[i]; bi = sidx[i]; }
+    float se = 0.f;
+    for (int v = threadIdx.x; v < V; v += blockDim.x)
+        if (v != mask_id) se += expf(row[v] - best);
+    se = block_sum(se, red);
+    if (threadIdx.x == 0) {
+        tok[c] = bi;
+        conf[c] = 1.0f / se;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Commit k positions per sequence: highest confidence first, ties to the lower position; or the
+// forced / pre-ordered positions. Updates tokens, mask bitmap, the previous-commit list and the logs.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void commit_kernel(CommitArgs a) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    __shared__ int chosen;
+    const int b = blockIdx.x;
+    const int c0 = a.cand_off[b], c1 = a.cand_off[b + 1];
+    for (int c = c0 + threadIdx.x; c < c1; c += 256) a.taken[c] = 0;
+    __syncthreads();
+    for (int j = 0; j < a.k; ++j) {
+        int pick = -1;        // candidate index
+        int want_pos = -1;
+        if (a.forced_pos) want_pos = a.forced_pos[b * a.k + j];
+        else if (a.order) want_pos = a.order[(size_t)b * a.G + a.step * a.k + j];
+        if (want_pos >= 0) {
+            if (threadIdx.x == 0) chosen = -1;
+            __syncthreads();
+            for (int c = c0 + threadIdx.x; c < c1; c += 256)
+                if (a.cand_pos[c] == want_pos) chosen = c;
+            __syncthreads();
+            pick = chosen;
+        } else {
+            float best = -INFINITY;
+            int bi = -1;
+            for (int c = c0 + threadIdx.x; c < c1; c += 256) {
+                float v = a.taken[c] ? -INFINITY : a.cand_conf[c];
+                if (bi < 0 || v > best) { best = v; bi = c; }   // ascending c = ascending position
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                float ob = __shfl_xor(best, o, 64);
+                int oi = __shfl_xor(bi, o, 64);
+                if (oi >= 0 && (bi < 0 || ob > best || (ob == best && oi < bi))) { best = ob; bi = oi; }
+            }
+            __syncthreads();
+            if ((threadIdx.x & 63) == 0) { sval[threadIdx.x >> 6] = best; sidx[threadIdx.x >> 6] = bi; }
+            __syncthreads();
+            best = sval[0]; bi = sidx[0];
+            for (int i = 1; i < 4; ++i)
+                if (sidx[i] >= 0 && (bi < 0 || sval[i] > best || (sval[i] == best && sidx[i] < bi))) {
+                    best = sval[i]; bi = sidx[i];
+                }
+            pick = (bi >= 0 && !(best == -INFINITY)) ? bi : -1;
+        }
+        if (threadIdx.x == 0) {
+            const size_t lo = ((size_t)a.step * a.batch + b) * a.k + j;
+            if (pick < 0) {
+                atomicOr(a.status, STATUS_BAD_COMMIT);
+                a.d_prev[b * a.k + j] = -1;
+                a.log_pos[lo] = -1; a.log_tok[lo] = -1; a.log_conf[lo] = 0.f;
+            } else {
+                const int p = a.cand_pos[pick];
+                const int t = a.forced_tok ? a.forced_tok[b * a.k + j] : a.cand_tok[pick];
+                a.tokens[(size_t)b * a.L + p] = t;
+                a.masked[(size_t)b * a.L + p] = 0;
+                a.taken[pick] = 1;
+                a.d_prev[b * a.k + j] = p;
+                a.log_pos[lo] = p; a.log_tok[lo] = t; a.log_conf[lo] = a.cand_conf[pick];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void init_state_kernel(int *tokens, uint8_t *masked, int *stamp, int *d_prev, int *status,
+                                  int batch, int L, int P, int k, int mask_id) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < (size_t)batch * L) {
+        const int p = (int)(i % L);
+        if (p >= P) tokens[i] = mask_id;
+        masked[i] = p >= P;
+        stamp[i] = -1;
+    }
+    if (i < (size_t)batch * k) d_prev[i] = -1;
+    if (i == 0) *status = 0;
+}
+
+__global__ void fill_i32_kernel(int *p, int v, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+__global__ void fill_u8_kernel(uint8_t *p, uint8_t v, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// k_cache[b][:, p, :] = k_new[r], v likewise (the scatter half of dkv_attn_update)
+template <typename T>
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const T *__restrict__ k_new,
+                                                           const T *__restrict__ v_new,
+                                                           const int *__restrict__ idx,
+                                                           const int *__restrict__ off, T *__restrict__ Kc,
+                                                           T *__restrict__ Vc, int batch, int Hkv, int L,
+                                                           int dh) {
+    const int r = blockIdx.x;
+    if (r >= off[batch]) return;
+    int b = 0;
+    while (r >= off[b + 1]) ++b;
+    const int p = idx[r];
+    for (int e = threadIdx.x; e < Hkv * dh; e += 256) {
+        const int h = e / dh, i = e % dh;
+        const size_t dst = (((size_t)b * Hkv + h) * L + p) * dh + i;
+        Kc[dst] = k_new[(size_t)r * Hkv * dh + e];
+        Vc[dst] = v_new[(size_t)r * Hkv * dh + e];
+    }
+}
+
+template <typename T> int vpt_dispatch_embed(hipStream_t s, int rows, int d, const T *embed, const int *tokens,
+                                             const int *row_pos, const int *row_seq, const int *counts,
+                                             const float *gain, float *h, T *a, int *stamp, int L, float eps,
+                                             int step) {
+#define GO(V)                                                                                              \
+    hipLaunchKernelGGL((embed_norm_kernel<T, V>), dim3(rows), dim3(256), 0, s, embed, tokens, row_pos,     \
+                       row_seq, counts, gain, h, a, stamp, L, d, eps, step)
+    if (d <= 256) GO(1);
+    else if (d <= 1024) GO(4);
+    else if (d <= 4096) GO(16);
+    else if (d <= 8192) GO(32);
+    else { dkv_set_error("d_model %d above 8192 is not supported", d); return DKV_E_UNSUPPORTED; }
+#undef GO
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+template <typename T> int vpt_dispatch_resnorm(hipStream_t s, int rows, int d, const float *part, int splits,
+                                               size_t stride, const int *counts, const float *gain, float *h,
+                                               T *a, float eps) {
+#define GO(V)                                                                                              \
+    hipLaunchKernelGGL((residual_norm_kernel<T, V>), dim3(rows), dim3(256), 0, s, part, splits, stride,    \
+                       counts, gain, h, a, d, eps)
+    if (d <= 256) GO(1);
+    else if (d <= 1024) GO(4);
+    else if (d <= 4096) GO(16);
+    else if (d <= 8192) GO(32);
+    else { dkv_set_error("d_model %d above 8192 is not supported", d); return DKV_E_UNSUPPORTED; }
+#undef GO
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------- launchers
+
+int dkv_launch_select(const SelectArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(select_active_kernel, dim3(1), dim3(1024), 0, s, a);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_embed_norm(int dtype, hipStream_t s, int rows, int d, const void *embed, const int *tokens,
+                          const int *row_pos, const int *row_seq, const int *counts, const float *gain,
+                          float *h, void *a, int *stamp, int L, float eps, int step) {
+    if (rows <= 0) return DKV_OK;
+    if (dtype == DKV_BF16)
+        return vpt_dispatch_embed<bf16_t>(s, rows, d, (const bf16_t *)embed, tokens, row_pos, row_seq, counts,
+                                          gain, h, (bf16_t *)a, stamp, L, eps, step);
+    return vpt_dispatch_embed<float>(s, rows, d, (const float *)embed, tokens, row_pos, row_seq, counts, gain,
+                                     h, (float *)a, stamp, L, eps, step);
+}
+
+int dkv_launch_residual_norm(int dtype, hipStream_t s, int rows, int d, const float *part, int splits,
+                             size_t stride, const int *counts, const float *gain, float *h, void *a,
+                             float eps) {
+    if (rows <= 0) return DKV_OK;
+    if (dtype == DKV_BF16)
+        return vpt_dispatch_resnorm<bf16_t>(s, rows, d, part, splits, stride, counts, gain, h, (bf16_t *)a,
+                                            eps);
+    return vpt_dispatch_resnorm<float>(s, rows, d, part, splits, stride, counts, gain, h, (float *)a, eps);
+}
+
+int dkv_launch_rope_scatter(int dtype, hipStream_t s, int rows, const float *part, int splits, size_t stride,
+                            const int *row_pos, const int *row_seq, const int *counts, const float *rope,
+                            void *q, void *Kc, void *Vc, int Hq, int Hkv, int dh, int L) {
+    if (rows <= 0) return DKV_OK;
+    if (dtype == DKV_BF16)
+        hipLaunchKernelGGL((rope_scatter_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, part, splits, stride,
+                           row_pos, row_seq, counts, (const float2 *)rope, (bf16_t *)q, (bf16_t *)Kc,
+                           (bf16_t *)Vc, Hq, Hkv, dh, L);
+    else
+        hipLaunchKernelGGL((rope_scatter_kernel<float>), dim3(rows), dim3(256), 0, s, part, splits, stride,
+                           row_pos, row_seq, counts, (const float2 *)rope, (float *)q, (float *)Kc,
+                           (float *)Vc, Hq, Hkv, dh, L);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_swiglu(int dtype, hipStream_t s, int rows, const float *part, int splits, size_t stride,
+                      const int *counts, void *f, int F) {
+    if (rows <= 0) return DKV_OK;
+    dim3 grid(ceil_div(F, 256), rows);
+    if (dtype == DKV_BF16)
+        hipLaunchKernelGGL((swiglu_kernel<bf16_t>), grid, dim3(256), 0, s, part, splits, stride, counts,
+                           (bf16_t *)f, F, 1);
+    else
+        hipLaunchKernelGGL((swiglu_kernel<float>), grid, dim3(256), 0, s, part, splits, stride, counts,
+                           (float *)f, F, 0);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_gather_rows(int dtype, hipStream_t s, int cands, const void *src, const int *cand_row,
+                           const int *counts, void *dst, int d) {
+    if (cands <= 0) return DKV_OK;
+    if (dtype == DKV_BF16)
+        hipLaunchKernelGGL((gather_rows_kernel<bf16_t>), dim3(cands), dim3(256), 0, s, (const bf16_t *)src,
+                           cand_row, counts, (bf16_t *)dst, d);
+    else
+        hipLaunchKernelGGL((gather_rows_kernel<float>), dim3(cands), dim3(256), 0, s, (const float *)src,
+                           cand_row, counts, (float *)dst, d);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_reduce_partials(hipStream_t s, const float *part, int splits, size_t stride, float *out,
+                               size_t total) {
+    if (total == 0) return DKV_OK;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, part,
+                       splits, stride, out, total);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_head_stats(hipStream_t s, int cands, const float *logits, const int *counts, int V,
+                          int mask_id, int *tok, float *conf, int *status) {
+    if (cands <= 0) return DKV_OK;
+    hipLaunchKernelGGL(head_stats_kernel, dim3(cands), dim3(1024), 0, s, logits, counts, V, mask_id, tok, conf,
+                       status);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_commit(const CommitArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(commit_kernel, dim3(a.batch), dim3(256), 0, s, a);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_init_state(hipStream_t s, int *tokens, uint8_t *masked, int *stamp, int *d_prev, int *status,
+                          int batch, int L, int P, int k, int mask_id) {
+    size_t n = (size_t)batch * L;
+    if ((size_t)batch * k > n) n = (size_t)batch * k;
+    hipLaunchKernelGGL(init_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, tokens, masked,
+                       stamp, d_prev, status, batch, L, P, k, mask_id);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_fill_i32(hipStream_t s, int *p, int v, size_t n) {
+    if (!n) return DKV_OK;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, v, n);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_fill_u8(hipStream_t s, uint8_t *p, uint8_t v, size_t n) {
+    if (!n) return DKV_OK;
+    hipLaunchKernelGGL(fill_u8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, v, n);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_scatter_rows(int dtype, hipStream_t s, int rows, const void *k_new, const void *v_new,
+                            const int *idx, const int *off, void *Kc, void *Vc, int batch, int Hkv, int L,
+                            int dh) {
+    if (rows <= 0) return DKV_OK;
+    if (dtype == DKV_BF16)
+        hipLaunchKernelGGL((scatter_rows_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, (const bf16_t *)k_new,
+                           (const bf16_t *)v_new, idx, off, (bf16_t *)Kc, (bf16_t *)Vc, batch, Hkv, L, dh);
+    else
+        hipLaunchKernelGGL((scatter_rows_kernel<float>), dim3(rows), dim3(256), 0, s, (const float *)k_new,
+                           (const float *)v_new, idx, off, (float *)Kc, (float *)Vc, batch, Hkv, L, dh);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}

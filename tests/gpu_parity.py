@@ -1,0 +1,95 @@
+"""Drives the HIP library and the oracle side by side on the same seeded inputs (GPU tests only)."""
+import numpy as np
+import torch
+
+import dkv_inputs as D
+from dkv_inputs.configs import BF16, FP32, RANDOM_ORDER
+from oracle import sampler as SA
+from helpers import rel_err
+
+
+def tolerances(dtype):
+    # relative bars of the build: 1e-2 for bf16 storage, 1e-5 in fp32 mode
+    return 1e-2 if dtype == BF16 else 1e-5
+
+
+def check_close(got, ref, tol, what):
+    l2, mx = rel_err(got, ref)
+    assert l2 <= tol and mx <= tol, f"{what}: rel L2 {l2:.3e}, rel max {mx:.3e} > {tol:.0e}"
+    return l2, mx
+
+
+def run_side_by_side(model, run, wseed, pseed, order_seed=None, teacher_forced=True, steps=None,
+                     forced_scopes=None, check_hidden=True, verbose=False):
+    """Steps both sides; asserts index state bit-exact and floats within tolerance.
+    Returns (gpu run object, oracle state)."""
+    import paper_2505_15781_amd as P
+    from paper_2505_15781_amd import binding
+    tol = tolerances(model.dtype)
+    synth = D.SynthWeights(model, wseed)
+    prompt = D.prompt_tokens(model, run, pseed)
+    order = D.random_block_order(run, order_seed) if run.remask == RANDOM_ORDER else None
+    w_dev = binding.upload_weights(model, synth)
+    g = P.DkvRun(model, run, w_dev, prompt, order=order)
+    st = SA.init_state(model, run, prompt)
+    B, k, V = run.batch, run.k_per_step, model.vocab
+    n_steps = run.steps if steps is None else steps
+    worst = {"logits": 0.0, "hidden": 0.0, "conf": 0.0}
+    for t in range(n_steps):
+        scope = None if forced_scopes is None else forced_scopes.get(t)
+        if scope is not None:
+            g.refresh(scope)
+        log = SA.denoise_step(model, synth, run, st, t, order=order, forced_scope=scope,
+                              keep_logits=True, keep_hidden=check_hidden)
+        ub = g.select_active(t)
+        pos, off = g.read_rows()
+        want_pos = np.concatenate([np.asarray(a, dtype=np.int32) for a in log.active])
+        want_off = np.concatenate([[0], np.cumsum([len(a) for a in log.active])]).astype(np.int32)
+        assert np.array_equal(off, want_off), f"step {t}: row offsets {off} != {want_off}"
+        assert np.array_equal(pos, want_pos), f"step {t}: active positions differ"
+        assert ub >= len(want_pos), f"step {t}: host bound {ub} below {len(want_pos)} rows"
+        n_cand = sum(len(c) for c in log.cand)
+        logits = torch.full((B * run.block_len, V), float("nan"), dtype=torch.float32, device="cuda")
+        fpos = ftok = None
+        if teacher_forced:
+            fpos = torch.as_tensor(log.pos, dtype=torch.int32, device="cuda").contiguous()
+            ftok = torch.as_tensor(log.tok, dtype=torch.int32, device="cuda").contiguous()
+        g.denoise_step(t, fpos, ftok, logits)
+        cpos, ctok, cconf, coff = g.read_candidates()
+        want_cpos = np.concatenate([np.asarray(c, dtype=np.int32) for c in log.cand])
+        assert np.array_equal(cpos, want_cpos), f"step {t}: candidate positions differ"
+        ref_logits = np.concatenate(log.cand_logits, axis=0)
+        got_logits = logits[:n_cand].cpu().numpy()
+        l2, mx = check_close(got_logits, ref_logits, tol, f"step {t} logits")
+        worst["logits"] = max(worst["logits"], l2, mx)
+        ref_conf = np.concatenate(log.cand_conf)
+        ref_tok = np.concatenate(log.cand_tok)
+        l2, mx = check_close(cconf, ref_conf, 4 * tol, f"step {t} confidence")
+        worst["conf"] = max(worst["conf"], l2, mx)
+        # arg max: identical, or the oracle's own logits of the two tokens are within tolerance
+        for i in np.nonzero(ctok != ref_tok)[0]:
+            gap = abs(ref_logits[i, ctok[i]] - ref_logits[i, ref_tok[i]])
+            assert gap <= tol * np.max(np.abs(ref_logits[i])), f"step {t} cand {i}: token {ctok[i]} vs {ref_tok[i]}, gap {gap}"
+            assert model.dtype == BF16, "fp32 mode must reproduce the oracle's tokens"
+        if check_hidden:
+            h = g.read_hidden()
+            l2, mx = check_close(h, log.hidden, tol, f"step {t} hidden")
+            worst["hidden"] = max(worst["hidden"], l2, mx)
+        dpos = g.decoded_pos[t].cpu().numpy()
+        dtok = g.decoded_tok[t].cpu().numpy()
+        if teacher_forced or model.dtype == FP32:
+            assert np.array_equal(dpos, log.pos), f"step {t}: committed positions {dpos} != {log.pos}"
+            assert np.array_equal(dtok, log.tok), f"step {t}: committed tokens differ"
+        else:
+            raise AssertionError("free-running bf16 comparison is not meaningful")
+        if verbose:
+            print(f"step {t}: rows {len(want_pos)} cands {n_cand} worst {worst}", flush=True)
+    assert np.array_equal(g.tokens.cpu().numpy(), st.tokens)
+    assert np.array_equal(g.masked.cpu().numpy().astype(bool), st.masked)
+    assert np.array_equal(g.stamp.cpu().numpy(), st.store.stamp)
+    # cache contents: every row ever written, against the oracle's store
+    Kg = g.k_cache.float().cpu().numpy()
+    Vg = g.v_cache.float().cpu().numpy()
+    check_close(Kg, st.store.K, tol, "K cache")
+    check_close(Vg, st.store.V, tol, "V cache")
+    return g, st, worst

@@ -1,0 +1,94 @@
+"""GPU parity of the isolated kernels (projection, cache update + attention) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import dkv_inputs as D
+from dkv_inputs.configs import BF16, FP32
+from oracle.attn_update import attn_update as oracle_attn_update
+from helpers import rel_err
+from gpu_parity import check_close, tolerances
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(x, dtype):
+    td = torch.bfloat16 if dtype == BF16 else torch.float32
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device="cuda", dtype=td)
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP32])
+@pytest.mark.parametrize("m,n,k", [(1, 128, 64), (2, 384, 4096), (37, 200, 136), (64, 256, 512),
+                                   (129, 384, 1024), (300, 130, 72), (513, 256, 256)])
+def test_projection_matches_float64_product(dtype, m, n, k):
+    import paper_2505_15781_amd as P
+    x = D.normal_f32(5, 1, (m, k), bf16=dtype == BF16)
+    w = D.normal_f32(5, 2, (n, k), std=0.02, bf16=dtype == BF16)
+    y = P.gemm(_dev(x, dtype), _dev(w, dtype), dtype).cpu().numpy()
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    check_close(y, ref, 1e-5, f"gemm {m}x{n}x{k}")
+
+
+def _attn_case(shape, n_active, seed, ragged=None):
+    import paper_2505_15781_amd as P
+    c = D.attn_update_case(shape, n_active, seed, ragged=ragged)
+    dt = shape.dtype
+    kc, vc = _dev(c["k_cache"], dt), _dev(c["v_cache"], dt)
+    rows = int(c["active_off"][-1])
+    max_rows = int(np.max(np.diff(c["active_off"]))) if shape.batch else 0
+    q, kn, vn = _dev(c["q"], dt), _dev(c["k_new"], dt), _dev(c["v_new"], dt)
+    idx = torch.from_numpy(c["active_idx"]).cuda()
+    off = torch.from_numpy(c["active_off"]).cuda()
+    out = torch.zeros((max(rows, 1), shape.n_q_heads, shape.head_dim), dtype=q.dtype, device="cuda")
+    nb = P.attn_update_workspace_bytes(shape.batch, shape.n_q_heads, shape.n_kv_heads, shape.seq_len,
+                                       shape.head_dim, dt, max_rows)
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    P.attn_update(kc, vc, q, kn, vn, idx, off, out, rows, max_rows, dt, ws)
+    torch.cuda.synchronize()
+    rk, rv = c["k_cache"].astype(np.float64), c["v_cache"].astype(np.float64)
+    ref = oracle_attn_update(rk, rv, c["q"], c["k_new"], c["v_new"], c["active_idx"], c["active_off"])
+    # the scatter is a copy: cache contents must be bit-exact
+    assert np.array_equal(kc.float().cpu().numpy().astype(np.float64), rk)
+    assert np.array_equal(vc.float().cpu().numpy().astype(np.float64), rv)
+    if rows:
+        check_close(out[:rows].float().cpu().numpy(), ref, tolerances(dt), f"attention A={n_active} {ragged}")
+
+
+@pytest.mark.parametrize("dh", [128, 64])
+def test_attention_small_ragged_gqa_bf16(dh):
+    shape = D.AttnUpdateShape(batch=3, n_q_heads=6, n_kv_heads=2, seq_len=203, head_dim=dh, dtype=BF16)
+    _attn_case(shape, None, 31, ragged=[5, 0, 37])
+    _attn_case(shape, None, 32, ragged=[1, 1, 1])
+    _attn_case(shape, None, 33, ragged=[203, 64, 17])
+
+
+def test_attention_generic_paths():
+    _attn_case(D.AttnUpdateShape(batch=2, n_q_heads=4, n_kv_heads=4, seq_len=70, head_dim=32, dtype=FP32),
+               None, 41, ragged=[9, 33])
+    _attn_case(D.AttnUpdateShape(batch=2, n_q_heads=4, n_kv_heads=2, seq_len=70, head_dim=32, dtype=BF16),
+               None, 42, ragged=[9, 33])
+    _attn_case(D.AttnUpdateShape(batch=1, n_q_heads=2, n_kv_heads=1, seq_len=40, head_dim=128, dtype=FP32),
+               None, 43, ragged=[7])
+
+
+def test_attention_no_rows_is_a_no_op():
+    shape = D.AttnUpdateShape(batch=2, n_q_heads=4, n_kv_heads=2, seq_len=64, head_dim=128, dtype=BF16)
+    _attn_case(shape, 0, 51)
+
+
+@pytest.mark.parametrize("n_active", D.CONFIG1_ACTIVE_SIZES)
+def test_attention_microbenchmark_configuration_full_size(n_active):
+    _attn_case(D.CONFIG1_SHAPE, n_active, 1100 + D.CONFIG1_ACTIVE_SIZES.index(n_active))
+
+
+def test_bad_arguments_are_errors_not_faults():
+    import paper_2505_15781_amd as P
+    shape = D.AttnUpdateShape(batch=1, n_q_heads=2, n_kv_heads=1, seq_len=40, head_dim=48, dtype=BF16)
+    kc = torch.zeros((1, 1, 40, 48), dtype=torch.bfloat16, device="cuda")
+    q = torch.zeros((1, 2, 48), dtype=torch.bfloat16, device="cuda")
+    kn = torch.zeros((1, 1, 48), dtype=torch.bfloat16, device="cuda")
+    idx = torch.zeros(1, dtype=torch.int32, device="cuda")
+    off = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    with pytest.raises(P.DkvError) as e:
+        P.attn_update(kc, kc.clone(), q, kn, kn, idx, off, q.clone(), 1, 1, BF16, None)
+    assert e.value.code == -3 and "head_dim" in str(e.value)
