@@ -169,6 +169,28 @@ int dkv_read_hidden(dkv_ctx *ctx, float *out, int32_t capacity_rows, int32_t *n_
 
 int dkv_destroy(dkv_ctx *ctx);
 
+/* Per-kernel timing for roofline reports. Between dkv_profile_begin and dkv_profile_end every
+ * launch of a projection or attention kernel made by dkv_denoise_step is bracketed by HIP events on
+ * the context's stream. dkv_profile_end synchronises the stream and fills `out` (host, array of
+ * DKV_PROF_KINDS entries) with, per kernel kind: number of launches, summed duration in
+ * milliseconds, and summed algorithmic bytes and flops of those launches:
+ *   projection  bytes = (M*K + N*K) * sizeof(element) + 4*M*N   flops = 2*M*N*K
+ *   attention   bytes = (2*batch*n_kv_heads*seq_len + 2*rows*n_q_heads) * head_dim * sizeof(element)
+ *               flops = 4*rows*n_q_heads*seq_len*head_dim
+ * with M the schedule's row count of the step. Kinds: */
+#define DKV_PROF_GEMM_BM32   0   /* projection, 32-row tiles  (M <= 32) */
+#define DKV_PROF_GEMM_BM64   1   /* projection, 64-row tiles  (M <= 64) */
+#define DKV_PROF_GEMM_BM128  2   /* projection, 128-row tiles (M > 64) */
+#define DKV_PROF_GEMM_FMA    3   /* projection, fp32 / generic kernel */
+#define DKV_PROF_ATTN        4   /* attention (including the key-slice merge when it runs) */
+#define DKV_PROF_KINDS       5
+typedef struct {
+    int64_t launches;
+    double ms, bytes, flops;
+} dkv_prof_entry;
+int dkv_profile_begin(dkv_ctx *ctx);
+int dkv_profile_end(dkv_ctx *ctx, dkv_prof_entry *out);
+
 /* Text of the last error raised on the calling thread ("" if none). Never NULL. */
 const char *dkv_last_error(void);
 

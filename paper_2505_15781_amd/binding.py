@@ -54,6 +54,16 @@ lib.dkv_read_rows.argtypes = [c_vp, c_vp, c_vp, c_i32, C.POINTER(c_i32)]
 lib.dkv_read_candidates.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, C.POINTER(c_i32)]
 lib.dkv_read_hidden.argtypes = [c_vp, c_vp, c_i32, C.POINTER(c_i32)]
 lib.dkv_destroy.argtypes = [c_vp]
+
+
+class ProfEntry(C.Structure):
+    _fields_ = [("launches", C.c_int64), ("ms", C.c_double), ("bytes", C.c_double), ("flops", C.c_double)]
+
+
+PROF_KINDS = ("gemm_bf16_mfma<1,1,1,4>", "gemm_bf16_mfma<2,1,1,4>", "gemm_bf16_mfma<2,2,2,2>", "gemm_simt",
+              "attention")
+lib.dkv_profile_begin.argtypes = [c_vp]
+lib.dkv_profile_end.argtypes = [c_vp, C.POINTER(ProfEntry)]
 lib.dkv_attn_update_workspace_bytes.restype = c_sz
 lib.dkv_attn_update_workspace_bytes.argtypes = [c_i32] * 7
 lib.dkv_attn_update.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp, c_sz, c_vp]
@@ -172,17 +182,40 @@ class DkvRun:
         self.workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=device)
         ws_ptr = (self.workspace.data_ptr() + 255) // 256 * 256
         self._arrs = {}
-        wd = Weights(_ptr(weights["embed"]), _ptr(weights["lm_head"]), _ptr(weights["final_norm"]))
+        self._wd = Weights(_ptr(weights["embed"]), _ptr(weights["lm_head"]), _ptr(weights["final_norm"]))
         for name in ("wqkv", "wo", "w_gate_up", "w_down", "norm1", "norm2"):
             arr = (c_vp * model.n_layers)(*[t.data_ptr() for t in weights[name]])
             self._arrs[name] = arr
-            setattr(wd, name, arr)
-        bd = Buffers(_ptr(self.k_cache), _ptr(self.v_cache), _ptr(self.tokens), _ptr(self.masked), _ptr(self.stamp),
-                     _ptr(self.decoded_pos), _ptr(self.decoded_tok), _ptr(self.decoded_conf), c_vp(ws_ptr), ws_bytes)
+            setattr(self._wd, name, arr)
+        self._bd = Buffers(_ptr(self.k_cache), _ptr(self.v_cache), _ptr(self.tokens), _ptr(self.masked),
+                           _ptr(self.stamp), _ptr(self.decoded_pos), _ptr(self.decoded_tok),
+                           _ptr(self.decoded_conf), c_vp(ws_ptr), ws_bytes)
         self.ctx = c_vp()
-        _check(lib.dkv_init_cache(C.byref(self.ctx), C.byref(self.md), C.byref(wd), C.byref(self.rd), C.byref(bd),
-                                  _stream()))
         self.workspace_bytes = ws_bytes
+        self._init()
+
+    def _init(self):
+        _check(lib.dkv_init_cache(C.byref(self.ctx), C.byref(self.md), C.byref(self._wd), C.byref(self.rd),
+                                  C.byref(self._bd), _stream()))
+
+    def reset(self):
+        """Start the run again on the same buffers (the prompt part of `tokens` is kept)."""
+        self.close()
+        self._init()
+
+    def generate(self, steps=None):
+        """Enqueue all denoising steps; no host synchronisation in between."""
+        for t in range(self.run.steps if steps is None else steps):
+            _check(lib.dkv_denoise_step(self.ctx, t, None, None, None))
+
+    def profile_begin(self):
+        _check(lib.dkv_profile_begin(self.ctx))
+
+    def profile_end(self):
+        arr = (ProfEntry * len(PROF_KINDS))()
+        _check(lib.dkv_profile_end(self.ctx, arr))
+        return {PROF_KINDS[i]: {"launches": arr[i].launches, "ms": arr[i].ms, "bytes": arr[i].bytes,
+                                "flops": arr[i].flops} for i in range(len(PROF_KINDS))}
 
     def select_active(self, step, active_idx=None, active_off=None):
         ub = c_i32(0)

@@ -150,9 +150,46 @@ struct dkv_ctx {
     int next_step, selected_step, forced_scope;
     int rows_upper, rows_per_seq_upper, cand_upper;
     int last_rows_upper, last_cand_upper;
+    // optional per-launch timing
+    bool prof_on = false;
+    struct ProfRec { hipEvent_t a, b; int kind; double bytes, flops; };
+    std::vector<ProfRec> prof;
+    std::vector<hipEvent_t> ev_pool;
 };
 
 namespace {
+
+int gemm_kind(int dtype, int k, const GemmPlan &p) {
+    if (dtype != DKV_BF16 || (k % 8)) return DKV_PROF_GEMM_FMA;
+    return p.bm == 32 ? DKV_PROF_GEMM_BM32 : (p.bm == 64 ? DKV_PROF_GEMM_BM64 : DKV_PROF_GEMM_BM128);
+}
+
+hipEvent_t prof_event(dkv_ctx *c) {
+    hipEvent_t e = nullptr;
+    if (!c->ev_pool.empty()) { e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Brackets the launches made by `fn` with events when profiling is on.
+template <typename F> int timed(dkv_ctx *c, int kind, double bytes, double flops, F fn) {
+    if (!c->prof_on) return fn();
+    hipEvent_t a = prof_event(c), b = prof_event(c);
+    if (!a || !b) { dkv_set_error("hipEventCreate failed"); return DKV_E_HIP; }
+    DKV_HIP_TRY(hipEventRecord(a, c->stream));
+    int rc = fn();
+    DKV_HIP_TRY(hipEventRecord(b, c->stream));
+    c->prof.push_back({a, b, kind, bytes, flops});
+    return rc;
+}
+
+int timed_gemm(dkv_ctx *c, const void *A, const void *W, float *out, int m, const int *m_dev, int n, int k,
+               GemmPlan p) {
+    const double es = (double)c->es;
+    return timed(c, gemm_kind(c->m.dtype, k, p), ((double)m * k + (double)n * k) * es + 4.0 * m * n,
+                 2.0 * m * n * k,
+                 [&] { return dkv_launch_gemm(c->m.dtype, A, W, out, m, m, m_dev, n, k, p, c->stream); });
+}
 
 template <typename P> P *ws(const dkv_ctx *c, size_t off) {
     return reinterpret_cast<P *>(static_cast<char *>(c->buf.workspace) + off);
@@ -344,21 +381,26 @@ extern "C" int dkv_denoise_step(dkv_ctx *c, int32_t step, const int32_t *forced_
         char *Kl = static_cast<char *>(c->buf.k_cache) + layer_elems * c->es * l;
         char *Vl = static_cast<char *>(c->buf.v_cache) + layer_elems * c->es * l;
         GemmPlan p = dkv_gemm_plan(dt, rows, nqkv, d);
-        if ((rc = dkv_launch_gemm(dt, c->a, c->wqkv[l], c->part, rows, rows, n_rows, nqkv, d, p, s))) return rc;
+        if ((rc = timed_gemm(c, c->a, c->wqkv[l], c->part, rows, n_rows, nqkv, d, p))) return rc;
         if ((rc = dkv_launch_rope_scatter(dt, s, rows, c->part, p.split_k, (size_t)rows * nqkv, c->row_pos, c->row_seq,
                                           c->counts, reinterpret_cast<const float *>(c->rope), c->q, Kl, Vl,
                                           m.n_q_heads, m.n_kv_heads, m.head_dim, c->L))) return rc;
-        if ((rc = dkv_launch_attention(dt, c->q, Kl, Vl, c->row_off, c->attn_out, r.batch, m.n_q_heads, m.n_kv_heads,
-                                       c->L, m.head_dim, rows, ap, c->attn_part, s))) return rc;
+        rc = timed(c, DKV_PROF_ATTN,
+                   (2.0 * r.batch * m.n_kv_heads * c->L + 2.0 * rows * m.n_q_heads) * m.head_dim * (double)c->es,
+                   4.0 * rows * m.n_q_heads * (double)c->L * m.head_dim, [&] {
+                       return dkv_launch_attention(dt, c->q, Kl, Vl, c->row_off, c->attn_out, r.batch, m.n_q_heads,
+                                                   m.n_kv_heads, c->L, m.head_dim, rows, ap, c->attn_part, s);
+                   });
+        if (rc) return rc;
         p = dkv_gemm_plan(dt, rows, d, qn);
-        if ((rc = dkv_launch_gemm(dt, c->attn_out, c->wo[l], c->part, rows, rows, n_rows, d, qn, p, s))) return rc;
+        if ((rc = timed_gemm(c, c->attn_out, c->wo[l], c->part, rows, n_rows, d, qn, p))) return rc;
         if ((rc = dkv_launch_residual_norm(dt, s, rows, d, c->part, p.split_k, (size_t)rows * d, c->counts, c->n2[l],
                                            c->h, c->a, m.rms_eps))) return rc;
         p = dkv_gemm_plan(dt, rows, 2 * m.d_ffn, d);
-        if ((rc = dkv_launch_gemm(dt, c->a, c->wgu[l], c->part, rows, rows, n_rows, 2 * m.d_ffn, d, p, s))) return rc;
+        if ((rc = timed_gemm(c, c->a, c->wgu[l], c->part, rows, n_rows, 2 * m.d_ffn, d, p))) return rc;
         if ((rc = dkv_launch_swiglu(dt, s, rows, c->part, p.split_k, (size_t)rows * 2 * m.d_ffn, c->counts, c->f, m.d_ffn))) return rc;
         p = dkv_gemm_plan(dt, rows, d, m.d_ffn);
-        if ((rc = dkv_launch_gemm(dt, c->f, c->wdown[l], c->part, rows, rows, n_rows, d, m.d_ffn, p, s))) return rc;
+        if ((rc = timed_gemm(c, c->f, c->wdown[l], c->part, rows, n_rows, d, m.d_ffn, p))) return rc;
         const float *next_gain = (l + 1 < m.n_layers) ? c->n1[l + 1] : c->final_norm;
         if ((rc = dkv_launch_residual_norm(dt, s, rows, d, c->part, p.split_k, (size_t)rows * d, c->counts, next_gain,
                                            c->h, c->a, m.rms_eps))) return rc;
@@ -368,9 +410,9 @@ extern "C" int dkv_denoise_step(dkv_ctx *c, int32_t step, const int32_t *forced_
     float *lg = logits_out ? logits_out : c->logits;
     GemmPlan hp = dkv_gemm_plan(dt, cands, m.vocab, d);
     if (hp.split_k == 1) {
-        if ((rc = dkv_launch_gemm(dt, c->a_c, c->lm_head, lg, cands, cands, n_cand, m.vocab, d, hp, s))) return rc;
+        if ((rc = timed_gemm(c, c->a_c, c->lm_head, lg, cands, n_cand, m.vocab, d, hp))) return rc;
     } else {
-        if ((rc = dkv_launch_gemm(dt, c->a_c, c->lm_head, c->part, cands, cands, n_cand, m.vocab, d, hp, s))) return rc;
+        if ((rc = timed_gemm(c, c->a_c, c->lm_head, c->part, cands, n_cand, m.vocab, d, hp))) return rc;
         if ((rc = dkv_launch_reduce_partials(s, c->part, hp.split_k, (size_t)cands * m.vocab, lg, (size_t)cands * m.vocab))) return rc;
     }
     if ((rc = dkv_launch_head_stats(s, cands, lg, c->counts, m.vocab, m.mask_id, c->cand_tok, c->cand_conf, c->status))) return rc;
@@ -452,7 +494,39 @@ extern "C" int dkv_read_hidden(dkv_ctx *c, float *out, int32_t capacity_rows, in
     return DKV_OK;
 }
 
+extern "C" int dkv_profile_begin(dkv_ctx *c) {
+    if (!c) { dkv_set_error("null context"); return DKV_E_INVALID_ARG; }
+    for (auto &r : c->prof) { c->ev_pool.push_back(r.a); c->ev_pool.push_back(r.b); }
+    c->prof.clear();
+    c->prof_on = true;
+    return DKV_OK;
+}
+
+extern "C" int dkv_profile_end(dkv_ctx *c, dkv_prof_entry *out) {
+    if (!c || !out) { dkv_set_error("null argument"); return DKV_E_INVALID_ARG; }
+    if (!c->prof_on) { dkv_set_error("profiling was not started"); return DKV_E_BAD_STATE; }
+    c->prof_on = false;
+    DKV_HIP_TRY(hipStreamSynchronize(c->stream));
+    for (int i = 0; i < DKV_PROF_KINDS; ++i) out[i] = dkv_prof_entry{0, 0.0, 0.0, 0.0};
+    for (auto &r : c->prof) {
+        float ms = 0.f;
+        DKV_HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+        out[r.kind].launches += 1;
+        out[r.kind].ms += ms;
+        out[r.kind].bytes += r.bytes;
+        out[r.kind].flops += r.flops;
+        c->ev_pool.push_back(r.a);
+        c->ev_pool.push_back(r.b);
+    }
+    c->prof.clear();
+    return DKV_OK;
+}
+
 extern "C" int dkv_destroy(dkv_ctx *c) {
+    if (c) {
+        for (auto &r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        for (auto e : c->ev_pool) (void)hipEventDestroy(e);
+    }
     delete c;
     return DKV_OK;
 }
