@@ -178,12 +178,15 @@ int dkv_destroy(dkv_ctx *ctx);
  *   attention   bytes = (2*batch*n_kv_heads*seq_len + 2*rows*n_q_heads) * head_dim * sizeof(element)
  *               flops = 4*rows*n_q_heads*seq_len*head_dim
  * with M the schedule's row count of the step. Kinds: */
-#define DKV_PROF_GEMM_BM32   0   /* projection, 32-row tiles  (M <= 32) */
-#define DKV_PROF_GEMM_BM64   1   /* projection, 64-row tiles  (M <= 64) */
-#define DKV_PROF_GEMM_BM128  2   /* projection, 128-row tiles (M > 64) */
-#define DKV_PROF_GEMM_FMA    3   /* projection, fp32 / generic kernel */
-#define DKV_PROF_ATTN        4   /* attention (including the key-slice merge when it runs) */
-#define DKV_PROF_KINDS       5
+#define DKV_GEMM_DMA_32x128   0   /* projection kernels by workgroup tile (rows x columns) */
+#define DKV_GEMM_DMA_64x128   1
+#define DKV_GEMM_DMA_128x128  2
+#define DKV_GEMM_DMA_128x256  3
+#define DKV_GEMM_DMA_256x256  4
+#define DKV_GEMM_REG_64x128   5   /* bf16 with K not a multiple of 64 */
+#define DKV_GEMM_SIMT         6   /* fp32 mode / generic */
+#define DKV_PROF_ATTN         7   /* attention (including the key-slice merge when it runs) */
+#define DKV_PROF_KINDS        8
 typedef struct {
     int64_t launches;
     double ms, bytes, flops;
@@ -219,6 +222,12 @@ int dkv_attn_update(void *k_cache, void *v_cache, const void *q, const void *k_n
 size_t dkv_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t dtype);
 int dkv_gemm(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k,
              int32_t dtype, void *workspace, size_t workspace_bytes, void *stream);
+/* The same with the kernel (DKV_GEMM_*) and the number of K slices chosen by the caller instead of the
+ * library's heuristic, so every kernel can be checked on every shape. workspace must hold
+ * split_k * m * n floats when split_k > 1. DKV_E_UNSUPPORTED if the kernel does not take the shape. */
+int dkv_gemm_with(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k,
+                  int32_t dtype, int32_t kind, int32_t split_k, void *workspace,
+                  size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -60,8 +60,10 @@ class ProfEntry(C.Structure):
     _fields_ = [("launches", C.c_int64), ("ms", C.c_double), ("bytes", C.c_double), ("flops", C.c_double)]
 
 
-PROF_KINDS = ("gemm_bf16_mfma<1,1,1,4>", "gemm_bf16_mfma<2,1,1,4>", "gemm_bf16_mfma<2,2,2,2>", "gemm_simt",
-              "attention")
+PROF_KINDS = ("gemm_dma<1,1,1,4,4>", "gemm_dma<2,1,1,4,4>", "gemm_dma<2,2,2,2,3>", "gemm_dma<2,4,2,2,3>",
+              "gemm_dma<4,4,2,2,2>", "gemm_reg", "gemm_simt", "attention")
+GEMM_KINDS = {"dma_32x128": 0, "dma_64x128": 1, "dma_128x128": 2, "dma_128x256": 3, "dma_256x256": 4,
+              "reg_64x128": 5, "simt": 6}
 lib.dkv_profile_begin.argtypes = [c_vp]
 lib.dkv_profile_end.argtypes = [c_vp, C.POINTER(ProfEntry)]
 lib.dkv_attn_update_workspace_bytes.restype = c_sz
@@ -70,6 +72,7 @@ lib.dkv_attn_update.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp, c_sz, c_vp]
 lib.dkv_gemm_workspace_bytes.restype = c_sz
 lib.dkv_gemm_workspace_bytes.argtypes = [c_i32] * 4
 lib.dkv_gemm.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_sz, c_vp]
+lib.dkv_gemm_with.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_vp, c_sz, c_vp]
 
 
 class DkvError(RuntimeError):
@@ -281,12 +284,18 @@ def attn_update(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, 
                                _stream()))
 
 
-def gemm(x, w, dtype):
-    """y = x @ w.T in fp32 through the library's projection kernel."""
+def gemm(x, w, dtype, kind=None, split_k=1):
+    """y = x @ w.T in fp32 through the library's projection kernel (heuristic choice unless `kind`)."""
     m, k = x.shape
     n = w.shape[0]
     y = torch.empty((m, n), dtype=torch.float32, device=x.device)
-    nb = lib.dkv_gemm_workspace_bytes(m, n, k, dtype)
-    ws = torch.empty(max(nb, 4), dtype=torch.uint8, device=x.device)
-    _check(lib.dkv_gemm(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, _ptr(ws), nb, _stream()))
+    if kind is None:
+        nb = lib.dkv_gemm_workspace_bytes(m, n, k, dtype)
+        ws = torch.empty(max(nb, 4), dtype=torch.uint8, device=x.device)
+        _check(lib.dkv_gemm(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, _ptr(ws), nb, _stream()))
+    else:
+        nb = split_k * m * n * 4 if split_k > 1 else 0
+        ws = torch.empty(max(nb, 4), dtype=torch.uint8, device=x.device)
+        _check(lib.dkv_gemm_with(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, GEMM_KINDS[kind], split_k, _ptr(ws),
+                                 nb, _stream()))
     return y

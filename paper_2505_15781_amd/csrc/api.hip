@@ -45,7 +45,7 @@ bool model_ok(const dkv_model_desc &m) {
     if (m.head_dim != 32 && m.head_dim != 64 && m.head_dim != 128) return false;
     if (m.mask_id < 0 || m.mask_id >= m.vocab) return false;
     if (m.dtype != DKV_BF16 && m.dtype != DKV_FP32) return false;
-    if (m.d_model > 8192) return false;
+    if (m.d_model > 8192 || m.d_model % 4 || m.d_ffn % 2) return false;
     return true;
 }
 
@@ -159,11 +159,6 @@ struct dkv_ctx {
 
 namespace {
 
-int gemm_kind(int dtype, int k, const GemmPlan &p) {
-    if (dtype != DKV_BF16 || (k % 8)) return DKV_PROF_GEMM_FMA;
-    return p.bm == 32 ? DKV_PROF_GEMM_BM32 : (p.bm == 64 ? DKV_PROF_GEMM_BM64 : DKV_PROF_GEMM_BM128);
-}
-
 hipEvent_t prof_event(dkv_ctx *c) {
     hipEvent_t e = nullptr;
     if (!c->ev_pool.empty()) { e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
@@ -186,7 +181,7 @@ template <typename F> int timed(dkv_ctx *c, int kind, double bytes, double flops
 int timed_gemm(dkv_ctx *c, const void *A, const void *W, float *out, int m, const int *m_dev, int n, int k,
                GemmPlan p) {
     const double es = (double)c->es;
-    return timed(c, gemm_kind(c->m.dtype, k, p), ((double)m * k + (double)n * k) * es + 4.0 * m * n,
+    return timed(c, p.kind, ((double)m * k + (double)n * k) * es + 4.0 * m * n,
                  2.0 * m * n * k,
                  [&] { return dkv_launch_gemm(c->m.dtype, A, W, out, m, m, m_dev, n, k, p, c->stream); });
 }
@@ -576,11 +571,17 @@ extern "C" size_t dkv_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int3
     return p.split_k > 1 ? (size_t)p.split_k * m * n * 4 : 0;
 }
 
-extern "C" int dkv_gemm(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k, int32_t dtype,
-                        void *workspace, size_t workspace_bytes, void *stream) {
+extern "C" int dkv_gemm_with(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k, int32_t dtype,
+                             int32_t kind, int32_t split_k, void *workspace, size_t workspace_bytes, void *stream) {
     if (!x || !w || !y || m < 1 || n < 1 || k < 1) { dkv_set_error("bad argument"); return DKV_E_INVALID_ARG; }
     if (dtype != DKV_BF16 && dtype != DKV_FP32) { dkv_set_error("unknown dtype"); return DKV_E_INVALID_ARG; }
-    GemmPlan p = dkv_gemm_plan(dtype, m, n, k);
+    GemmPlan p;
+    p.kind = kind;
+    p.split_k = split_k;
+    if (!dkv_gemm_plan_valid(dtype, k, p)) {
+        dkv_set_error("kernel %d with %d K slices does not take dtype %d, K %d", kind, split_k, dtype, k);
+        return DKV_E_UNSUPPORTED;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (p.split_k == 1) return dkv_launch_gemm(dtype, x, w, y, m, m, nullptr, n, k, p, s);
     size_t need = (size_t)p.split_k * m * n * 4;
@@ -592,4 +593,11 @@ extern "C" int dkv_gemm(const void *x, const void *w, float *y, int32_t m, int32
     if (rc) return rc;
     return dkv_launch_reduce_partials(s, static_cast<const float *>(workspace), p.split_k, (size_t)m * n, y,
                                       (size_t)m * n);
+}
+
+extern "C" int dkv_gemm(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k, int32_t dtype,
+                        void *workspace, size_t workspace_bytes, void *stream) {
+    if (m < 1 || n < 1 || k < 1) { dkv_set_error("bad argument"); return DKV_E_INVALID_ARG; }
+    GemmPlan p = dkv_gemm_plan(dtype, m, n, k);
+    return dkv_gemm_with(x, w, y, m, n, k, dtype, p.kind, p.split_k, workspace, workspace_bytes, stream);
 }

@@ -77,11 +77,14 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // ---- internal launchers (host side) --------------------------------------------------------
 
 // Plan of one projection: tile shape and split of the K dimension.
+enum { GEMM_DMA_32x128 = 0, GEMM_DMA_64x128, GEMM_DMA_128x128, GEMM_DMA_128x256, GEMM_DMA_256x256,
+       GEMM_REG_64x128, GEMM_SIMT, GEMM_KINDS };
 struct GemmPlan {
-    int bm;        // rows per workgroup tile
+    int kind;      // GEMM_* kernel and tile shape
     int split_k;   // number of K slices; slice s writes partial[s]
 };
 GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k);
+int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p);
 
 // partial[s][m][n] (fp32, stride m_cap rows per slice) = A[m, k-slice] * W[n, k-slice]^T.
 // Rows >= *m_dev (when m_dev != nullptr) are neither read nor written.

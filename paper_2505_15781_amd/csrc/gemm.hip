@@ -1,66 +1,82 @@
 // Projection kernels: partial[s][m][n] = A[m, k-slice s] * W[n, k-slice s]^T, fp32 accumulation.
 //
-// bf16: MFMA 32x32x16 tiles, 256 threads (4 wavefronts) per workgroup, A and W tiles staged through
-// LDS in 16-byte chunks (XOR-swizzled by row so fragment reads spread over the banks), global
-// loads of the next K tile in flight while the current one is multiplied.
-// fp32 (and any shape the MFMA kernel does not take): a plain FMA tile kernel.
-//
 // The active rows of a denoising step (Algorithm 1 line 3: the transformer runs on x[M_{t-1}] only)
 // are the M dimension; their count lives on the device, so kernels bound M by *m_dev.
+//
+// bf16, K a multiple of 64 (every model shape): `gemm_dma`. MFMA 32x32x16 tiles; the A and W tiles of
+// a K step travel from global memory straight into LDS (global_load_lds_dwordx4: 16 bytes per lane, lane i
+// lands at base + 16 i) through a ring of STAGES buffers, so up to STAGES-1 tiles are in flight without
+// holding registers. The LDS layout XOR-swizzles the 16-byte chunks of a 128-byte row with (row >> 1)
+// so a fragment read of 16 consecutive rows touches every bank once; the swizzle is applied by choosing
+// which global chunk each lane fetches. Fragment reads run one K sub-step ahead of the MFMAs, across tile
+// boundaries. Measured on MI355X a compute unit sustains about 60 GB/s of such fills whatever the depth,
+// so the tile shapes below are chosen to keep the bytes each workgroup pulls (W tile + A tile) small
+// relative to its MFMA work, and K is split across workgroups only as far as needed to fill 256 CUs.
+// bf16, other K (multiple of 8): `gemm_reg`, register-staged tiles. fp32 mode / anything else: `gemm_simt`.
 #include "common.h"
 
 namespace {
 
 constexpr int BK = 64;   // K elements per LDS tile (8 chunks of 8 bf16)
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
-template <int MT, int NT, int WM, int WN>
-__global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t *__restrict__ A,
-                                                      const bf16_t *__restrict__ W,
-                                                      float *__restrict__ P, int m_upper, int m_cap,
-                                                      const int *__restrict__ m_dev, int N, int K,
-                                                      int kt_per_split) {
-    constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
-    constexpr int CA = BM / 32, CW = BN / 32;            // 16-byte chunks per thread per tile
-    __shared__ uint4 lds[2][(BM + BN) * 8];
+// 16 bytes per lane from global memory into LDS at lds_addr + 16 * lane (lds_addr wave-uniform).
+// Issued through inline assembly so that the compiler does not serialise the ring on its own
+// conservative wait; completion is awaited explicitly with vmcnt below.
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
+}
+// s_waitcnt immediate: vmcnt(n) [bits 3:0 and 15:14], lgkmcnt(0) when `lgkm0`, expcnt untouched
+__device__ __forceinline__ constexpr int waitcnt_imm(int n, bool lgkm0) {
+    return (n & 15) | ((n >> 4) << 14) | 0x0070 | (lgkm0 ? 0 : 0x0F00);
+}
+
+template <int MT, int NT, int WM, int WN, int STAGES>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restrict__ A,
+                                                         const bf16_t *__restrict__ W, float *__restrict__ P,
+                                                         int m_upper, int m_cap,
+                                                         const int *__restrict__ m_dev, int N, int K,
+                                                         int kt_per_split) {
+    constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN, NW = WM * WN;
+    constexpr int CA = BM / (8 * NW), CW = BN / (8 * NW);     // load instructions per thread per tile
+    constexpr int STAGE_CHUNKS = (BM + BN) * 8;
+    static_assert((STAGES - 2) * (CA + CW) < 64, "vmcnt is a 6-bit counter");
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];
 
     const int M = m_dev ? min(*m_dev, m_upper) : m_upper;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     if (m0 >= M) return;
-    const int kt_total = (K + BK - 1) / BK;
+    const int kt_total = K / BK;
     const int kt0 = blockIdx.z * kt_per_split;
-    const int kt1 = min(kt_total, kt0 + kt_per_split);
-
+    const int nk = min(kt_total, kt0 + kt_per_split) - kt0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds_base = (uint32_t)(size_t)(lds_ptr_t)lds;
 
-    uint4 ra[CA], rw[CW];
-    auto load_global = [&](int kt) {
+    // Source pointer of each load instruction for K tile kt0. Slot s of a stage holds row s/8, and in
+    // position s%8 the chunk (s%8) ^ ((row>>1)&7). Rows past the end are clamped: they only feed outputs
+    // that are never stored.
+    const bf16_t *pa[CA], *pw[CW];
 #pragma unroll
-        for (int i = 0; i < CA; ++i) {
-            int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-            int gm = m0 + row, gk = kt * BK + kc * 8;
-            ra[i] = (gm < M && gk < K) ? *reinterpret_cast<const uint4 *>(A + (size_t)gm * K + gk)
-                                       : make_uint4(0, 0, 0, 0);
-        }
+    for (int i = 0; i < CA; ++i) {
+        int s = (i * NW + wave) * 64 + lane, row = s >> 3, kc = (s & 7) ^ ((row >> 1) & 7);
+        pa[i] = A + (size_t)min(m0 + row, M - 1) * K + (size_t)kt0 * BK + kc * 8;
+    }
 #pragma unroll
-        for (int i = 0; i < CW; ++i) {
-            int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-            int gn = n0 + row, gk = kt * BK + kc * 8;
-            rw[i] = (gn < N && gk < K) ? *reinterpret_cast<const uint4 *>(W + (size_t)gn * K + gk)
-                                       : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto store_lds = [&](int buf) {
+    for (int i = 0; i < CW; ++i) {
+        int s = (i * NW + wave) * 64 + lane, row = s >> 3, kc = (s & 7) ^ ((row >> 1) & 7);
+        pw[i] = W + (size_t)min(n0 + row, N - 1) * K + (size_t)kt0 * BK + kc * 8;
+    }
+    // Tiles past the slice are clamped to its last tile: the load count per step stays constant (so one
+    // vmcnt value fits every iteration) and the redundant data lands in a stage nobody reads.
+    auto issue = [&](int t, int stage) {
+        const size_t koff = (size_t)min(t, nk - 1) * BK;
+        const uint32_t base = lds_base + (uint32_t)(stage * STAGE_CHUNKS + wave_u * 64) * 16u;
 #pragma unroll
-        for (int i = 0; i < CA; ++i) {
-            int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-            lds[buf][row * 8 + (kc ^ (row & 7))] = ra[i];
-        }
+        for (int i = 0; i < CA; ++i) dma16(pa[i] + koff, base + (uint32_t)(i * NW * 64) * 16u);
 #pragma unroll
-        for (int i = 0; i < CW; ++i) {
-            int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-            lds[buf][(BM + row) * 8 + (kc ^ (row & 7))] = rw[i];
-        }
+        for (int i = 0; i < CW; ++i) dma16(pw[i] + koff, base + (uint32_t)(BM * 8 + i * NW * 64) * 16u);
     };
 
     f32x16 acc[MT][NT];
@@ -71,38 +87,50 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t *__restrict__
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    if (kt0 < kt1) {
-        load_global(kt0);
-        store_lds(0);
-    }
-    __syncthreads();
-    for (int kt = kt0; kt < kt1; ++kt) {
-        const int buf = (kt - kt0) & 1;
-        if (kt + 1 < kt1) load_global(kt + 1);
-        const bf16x8 *tile = reinterpret_cast<const bf16x8 *>(lds[buf]);
+    bf16x8 af[2][MT], wf[2][NT];
+    auto ldfrag = [&](int stage, int ks, int fb) {
+        const bf16x8 *tile = reinterpret_cast<const bf16x8 *>(lds + stage * STAGE_CHUNKS);
+        const int chunk = 2 * ks + (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            int row = (wm * MT + i) * 32 + (lane & 31);
+            af[fb][i] = tile[row * 8 + (chunk ^ ((row >> 1) & 7))];
+        }
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            int row = (wn * NT + j) * 32 + (lane & 31);
+            wf[fb][j] = tile[(BM + row) * 8 + (chunk ^ ((row >> 1) & 7))];
+        }
+    };
+    // Make tile `next` readable: this wave's part of it has landed (all but the newest STAGES-2 tiles'
+    // loads are done) and its own LDS reads have returned; after the barrier that holds for every wave, so
+    // the stage read until now can be refilled and the first fragments of `next` fetched.
+    auto advance = [&](int next) {
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 2) * (CA + CW), true));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue(next + STAGES - 1, (next + STAGES - 1) % STAGES);
+        ldfrag(next % STAGES, 0, 0);
+    };
+
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue(s, s);
+    advance(0);
+    for (int t = 0; t < nk; ++t) {
+        const int stage = t % STAGES;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            const int chunk = 2 * ks + (lane >> 5);
-            bf16x8 af[MT], wf[NT];
-#pragma unroll
-            for (int i = 0; i < MT; ++i) {
-                int row = (wm * MT + i) * 32 + (lane & 31);
-                af[i] = tile[row * 8 + (chunk ^ (row & 7))];
-            }
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                int row = (wn * NT + j) * 32 + (lane & 31);
-                wf[j] = tile[(BM + row) * 8 + (chunk ^ (row & 7))];
-            }
+            if (ks + 1 < BK / 16) ldfrag(stage, ks + 1, (ks + 1) & 1);
+            else if (t + 1 < nk) advance(t + 1);
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
                 for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], wf[ks & 1][j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < kt1) store_lds(buf ^ 1);
-        __syncthreads();
     }
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));   // the clamped tail loads must land before LDS is released
 
     float *out = P + (size_t)blockIdx.z * m_cap * N;
 #pragma unroll
@@ -118,27 +146,102 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t *__restrict__
         }
 }
 
+// Register-staged variant for K that is a multiple of 8 but not of 64 (zero-fills the K tail).
+__global__ __launch_bounds__(256) void gemm_reg(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
+                                                float *__restrict__ P, int m_upper, int m_cap,
+                                                const int *__restrict__ m_dev, int N, int K, int kt_per_split) {
+    constexpr int MT = 2, BM = 64, BN = 128, CA = 2, CW = 4;
+    __shared__ uint4 lds[2][(BM + BN) * 8];
+    const int M = m_dev ? min(*m_dev, m_upper) : m_upper;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    if (m0 >= M) return;
+    const int kt_total = (K + BK - 1) / BK;
+    const int kt0 = blockIdx.z * kt_per_split, kt1 = min(kt_total, kt0 + kt_per_split);
+    const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
+    uint4 ra[CA], rw[CW];
+    auto load_global = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) {
+            int c = tid + 256 * i, row = c >> 3, kc = c & 7, gm = m0 + row, gk = kt * BK + kc * 8;
+            ra[i] = (gm < M && gk < K) ? *reinterpret_cast<const uint4 *>(A + (size_t)gm * K + gk) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < CW; ++i) {
+            int c = tid + 256 * i, row = c >> 3, kc = c & 7, gn = n0 + row, gk = kt * BK + kc * 8;
+            rw[i] = (gn < N && gk < K) ? *reinterpret_cast<const uint4 *>(W + (size_t)gn * K + gk) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) {
+            int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+            lds[buf][row * 8 + (kc ^ ((row >> 1) & 7))] = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < CW; ++i) {
+            int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+            lds[buf][(BM + row) * 8 + (kc ^ ((row >> 1) & 7))] = rw[i];
+        }
+    };
+    f32x16 acc[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    if (kt0 < kt1) {
+        load_global(kt0);
+        store_lds(0);
+    }
+    __syncthreads();
+    for (int kt = kt0; kt < kt1; ++kt) {
+        const int buf = (kt - kt0) & 1;
+        if (kt + 1 < kt1) load_global(kt + 1);
+        const bf16x8 *tile = reinterpret_cast<const bf16x8 *>(lds[buf]);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int chunk = 2 * ks + (lane >> 5);
+            const int wrow = wn * 32 + (lane & 31);
+            const bf16x8 wfr = tile[(BM + wrow) * 8 + (chunk ^ ((wrow >> 1) & 7))];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                const int row = i * 32 + (lane & 31);
+                const bf16x8 afr = tile[row * 8 + (chunk ^ ((row >> 1) & 7))];
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afr, wfr, acc[i], 0, 0, 0);
+            }
+        }
+        if (kt + 1 < kt1) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+    float *out = P + (size_t)blockIdx.z * m_cap * N;
+    const int n = n0 + wn * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = m0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (m < M && n < N) out[(size_t)m * N + n] = acc[i][v];
+        }
+}
+
 // Plain FMA tile kernel: 64x64 outputs per workgroup, 4x4 per thread.
 template <typename T>
 __global__ __launch_bounds__(256) void gemm_simt(const T *__restrict__ A, const T *__restrict__ W,
-                                                 float *__restrict__ P, int m_upper, int m_cap,
-                                                 const int *__restrict__ m_dev, int N, int K,
-                                                 int k_per_split) {
+                                                 float *__restrict__ P, int m_upper,
+                                                 const int *__restrict__ m_dev, int N, int K) {
     constexpr int TM = 64, TN = 64, TK = 16;
     __shared__ float As[TK][TM + 4], Ws[TK][TN + 4];
     const int M = m_dev ? min(*m_dev, m_upper) : m_upper;
     const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
     if (m0 >= M) return;
-    const int k0 = blockIdx.z * k_per_split, k1 = min(K, k0 + k_per_split);
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     float acc[4][4] = {};
-    for (int kb = k0; kb < k1; kb += TK) {
+    for (int kb = 0; kb < K; kb += TK) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             int e = tid + 256 * i, row = e >> 4, kk = e & 15;
             int gk = kb + kk;
-            As[kk][row] = (m0 + row < M && gk < k1) ? El<T>::ld(A + (size_t)(m0 + row) * K + gk) : 0.f;
-            Ws[kk][row] = (n0 + row < N && gk < k1) ? El<T>::ld(W + (size_t)(n0 + row) * K + gk) : 0.f;
+            As[kk][row] = (m0 + row < M && gk < K) ? El<T>::ld(A + (size_t)(m0 + row) * K + gk) : 0.f;
+            Ws[kk][row] = (n0 + row < N && gk < K) ? El<T>::ld(W + (size_t)(n0 + row) * K + gk) : 0.f;
         }
         __syncthreads();
 #pragma unroll
@@ -155,68 +258,125 @@ __global__ __launch_bounds__(256) void gemm_simt(const T *__restrict__ A, const 
         }
         __syncthreads();
     }
-    float *out = P + (size_t)blockIdx.z * m_cap * N;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-            if (m < M && n < N) out[(size_t)m * N + n] = acc[i][j];
+            if (m < M && n < N) P[(size_t)m * N + n] = acc[i][j];
         }
 }
 
-template <int MT, int NT, int WM, int WN>
-void launch_mfma(const void *A, const void *W, float *P, int m_upper, int m_cap, const int *m_dev, int n,
-                 int k, int split, hipStream_t s) {
+struct KindInfo {
+    int bm, bn;
+};
+constexpr KindInfo kKinds[] = {
+    {32, 128},    // GEMM_DMA_32x128   <1,1,1,4> 4 stages
+    {64, 128},    // GEMM_DMA_64x128   <2,1,1,4> 4 stages
+    {128, 128},   // GEMM_DMA_128x128  <2,2,2,2> 3 stages
+    {128, 256},   // GEMM_DMA_128x256  <2,4,2,2> 3 stages
+    {256, 256},   // GEMM_DMA_256x256  <4,4,2,2> 2 stages
+};
+
+template <int MT, int NT, int WM, int WN, int STAGES>
+int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, const int *m_dev, int n, int k,
+               int split, hipStream_t s) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
-    int kt_total = ceil_div(k, BK), kps = ceil_div(kt_total, split);
+    constexpr int smem = STAGES * (BM + BN) * 128;
+    static bool attr_set = false;
+    if (!attr_set) {
+        DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_dma<MT, NT, WM, WN, STAGES>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        attr_set = true;
+    }
+    const int kt_total = k / BK, kps = ceil_div(kt_total, split);
     dim3 grid(ceil_div(n, BN), ceil_div(m_upper, BM), ceil_div(kt_total, kps));
-    hipLaunchKernelGGL((gemm_bf16_mfma<MT, NT, WM, WN>), grid, dim3(256), 0, s, (const bf16_t *)A,
+    hipLaunchKernelGGL((gemm_dma<MT, NT, WM, WN, STAGES>), grid, dim3(64 * WM * WN), smem, s, (const bf16_t *)A,
                        (const bf16_t *)W, P, m_upper, m_cap, m_dev, n, k, kps);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+// Number of K slices that is really launched for a requested split (no empty slice).
+int effective_split(int k, int split) {
+    const int kt_total = ceil_div(k, BK), kps = ceil_div(kt_total, split < 1 ? 1 : split);
+    return ceil_div(kt_total, kps);
 }
 
 }  // namespace
 
 GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     GemmPlan p;
+    p.split_k = 1;
     if (dtype != DKV_BF16 || (k % 8) != 0) {
-        p.bm = 64;
-        p.split_k = 1;
+        p.kind = GEMM_SIMT;
         return p;
     }
-    p.bm = m_upper <= 32 ? 32 : (m_upper <= 64 ? 64 : 128);
-    int tiles = ceil_div(m_upper, p.bm) * ceil_div(n, 128);
-    int kt_total = ceil_div(k, BK);
-    int s = 1;
-    if (tiles < 256) {
-        s = ceil_div(512, tiles);
-        int max_s = kt_total / 4 > 0 ? kt_total / 4 : 1;
-        if (s > max_s) s = max_s;
-        if (s > 16) s = 16;
+    if (k % BK != 0) {
+        p.kind = GEMM_REG_64x128;
+        return p;
     }
-    int kps = ceil_div(kt_total, s);
-    p.split_k = ceil_div(kt_total, kps);
+    const bool wide = n >= 8192;
+    if (m_upper <= 32) p.kind = GEMM_DMA_32x128;
+    else if (m_upper <= 64) p.kind = GEMM_DMA_64x128;
+    else if (m_upper <= 128) p.kind = GEMM_DMA_128x128;
+    else if (!wide) p.kind = m_upper >= 1024 ? GEMM_DMA_256x256 : GEMM_DMA_128x128;
+    else if (m_upper <= 384) p.kind = GEMM_DMA_128x256;
+    else p.kind = GEMM_DMA_256x256;
+    const KindInfo &ki = kKinds[p.kind];
+    const int tiles = ceil_div(m_upper, ki.bm) * ceil_div(n, ki.bn);
+    int s = 320 / tiles;
+    const int kt_total = k / BK;
+    const int max_s = kt_total / 8 > 0 ? kt_total / 8 : 1;      // at least 8 K tiles per slice
+    if (s > 8) s = 8;
+    if (s > max_s) s = max_s;
+    if (s < 1) s = 1;
+    p.split_k = effective_split(k, s);
     return p;
 }
 
+int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p) {
+    if (p.split_k < 1 || p.kind < 0 || p.kind >= GEMM_KINDS) return 0;
+    if (p.kind == GEMM_SIMT) return p.split_k == 1;
+    if (dtype != DKV_BF16 || (k % 8) != 0) return 0;
+    if (p.kind != GEMM_REG_64x128 && (k % BK) != 0) return 0;
+    return effective_split(k, p.split_k) == p.split_k;
+}
+
 int dkv_launch_gemm(int dtype, const void *A, const void *W, float *partial, int m_upper, int m_cap,
-                    const int *m_dev, int n, int k, GemmPlan plan, hipStream_t stream) {
+                    const int *m_dev, int n, int k, GemmPlan p, hipStream_t stream) {
     if (m_upper <= 0) return DKV_OK;
-    if (dtype == DKV_BF16 && (k % 8) == 0) {
-        if (plan.bm == 32)
-            launch_mfma<1, 1, 1, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, plan.split_k, stream);
-        else if (plan.bm == 64)
-            launch_mfma<2, 1, 1, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, plan.split_k, stream);
-        else
-            launch_mfma<2, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, plan.split_k, stream);
-    } else {
-        dim3 grid(ceil_div(n, 64), ceil_div(m_upper, 64), 1);
-        if (dtype == DKV_BF16)
-            hipLaunchKernelGGL((gemm_simt<bf16_t>), grid, dim3(256), 0, stream, (const bf16_t *)A,
-                               (const bf16_t *)W, partial, m_upper, m_cap, m_dev, n, k, k);
-        else
-            hipLaunchKernelGGL((gemm_simt<float>), grid, dim3(256), 0, stream, (const float *)A,
-                               (const float *)W, partial, m_upper, m_cap, m_dev, n, k, k);
+    if (!dkv_gemm_plan_valid(dtype, k, p)) {
+        dkv_set_error("projection plan (kind %d, split %d) does not fit dtype %d, K %d", p.kind, p.split_k, dtype, k);
+        return DKV_E_UNSUPPORTED;
+    }
+    switch (p.kind) {
+        case GEMM_DMA_32x128:
+            return launch_dma<1, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+        case GEMM_DMA_64x128:
+            return launch_dma<2, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+        case GEMM_DMA_128x128:
+            return launch_dma<2, 2, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+        case GEMM_DMA_128x256:
+            return launch_dma<2, 4, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+        case GEMM_DMA_256x256:
+            return launch_dma<4, 4, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+        case GEMM_REG_64x128: {
+            const int kt_total = ceil_div(k, BK), kps = ceil_div(kt_total, p.split_k);
+            dim3 grid(ceil_div(n, 128), ceil_div(m_upper, 64), p.split_k);
+            hipLaunchKernelGGL(gemm_reg, grid, dim3(256), 0, stream, (const bf16_t *)A, (const bf16_t *)W, partial,
+                               m_upper, m_cap, m_dev, n, k, kps);
+            break;
+        }
+        default: {
+            dim3 grid(ceil_div(n, 64), ceil_div(m_upper, 64), 1);
+            if (dtype == DKV_BF16)
+                hipLaunchKernelGGL((gemm_simt<bf16_t>), grid, dim3(256), 0, stream, (const bf16_t *)A,
+                                   (const bf16_t *)W, partial, m_upper, m_dev, n, k);
+            else
+                hipLaunchKernelGGL((gemm_simt<float>), grid, dim3(256), 0, stream, (const float *)A,
+                                   (const float *)W, partial, m_upper, m_dev, n, k);
+        }
     }
     DKV_LAUNCH_CHECK();
     return DKV_OK;

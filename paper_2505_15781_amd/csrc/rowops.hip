@@ -128,7 +128,18 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ e
 // ------------------------------------------------------------------------------------------------
 // h[r] += sum_s partial[s][r]; a[r] = RMSNorm(h[r]) * gain (the next projection's input).
 // ------------------------------------------------------------------------------------------------
-template <typename T, int VPT>
+// four consecutive outputs as one store
+__device__ __forceinline__ void store4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ __forceinline__ void store4(bf16_t *p, float4 v) {
+    uint2 w;
+    w.x = (uint32_t)f2bf(v.x) | ((uint32_t)f2bf(v.y) << 16);
+    w.y = (uint32_t)f2bf(v.z) | ((uint32_t)f2bf(v.w) << 16);
+    *reinterpret_cast<uint2 *>(p) = w;
+}
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+
+// one workgroup per row, float4 per lane: d must be a multiple of 4 and at most 1024 * V4
+template <typename T, int V4>
 __global__ __launch_bounds__(256) void residual_norm_kernel(const float *__restrict__ part, int splits,
                                                             size_t split_stride,
                                                             const int *__restrict__ counts,
@@ -138,26 +149,31 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(const float *__restr
     __shared__ float red[16];
     const int r = blockIdx.x;
     if (r >= counts[0]) return;
-    float v[VPT], ss = 0.f;
+    float4 v[V4];
+    float ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-        int c = threadIdx.x + 256 * i;
-        float x = 0.f;
+    for (int i = 0; i < V4; ++i) {
+        const int c = (threadIdx.x + 256 * i) * 4;
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
         if (c < d) {
-            x = h[(size_t)r * d + c];
-            for (int s = 0; s < splits; ++s) x += part[s * split_stride + (size_t)r * d + c];
+            const size_t at = (size_t)r * d + c;
+            x = *reinterpret_cast<const float4 *>(h + at);
+#pragma unroll 4
+            for (int s = 0; s < splits; ++s) x = add4(x, *reinterpret_cast<const float4 *>(part + s * split_stride + at));
         }
         v[i] = x;
-        ss += x * x;
+        ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
     }
     ss = block_sum(ss, red);
     const float rs = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-        int c = threadIdx.x + 256 * i;
+    for (int i = 0; i < V4; ++i) {
+        const int c = (threadIdx.x + 256 * i) * 4;
         if (c < d) {
-            h[(size_t)r * d + c] = v[i];
-            El<T>::st(a + (size_t)r * d + c, v[i] * rs * gain[c]);
+            const size_t at = (size_t)r * d + c;
+            *reinterpret_cast<float4 *>(h + at) = v[i];
+            const float4 g = *reinterpret_cast<const float4 *>(gain + c);
+            store4(a + at, make_float4(v[i].x * rs * g.x, v[i].y * rs * g.y, v[i].z * rs * g.z, v[i].w * rs * g.w));
         }
     }
 }
@@ -166,7 +182,7 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(const float *__restr
 // Rotary embedding of q and k with the row's true position (Appendix A: positional embeddings follow
 // the token), q to its row buffer, k and v to the cache rows of that position (Algorithm 1 line 4,
 // position-indexed instead of concatenated).
-// qkv partials: [splits][rows][(Hq + 2 Hkv) * dh] fp32. rope: [L][dh/2] (cos, sin).
+// qkv partials: [splits][rows][(Hq + 2 Hkv) * dh] fp32. rope: [L][dh/2] (cos, sin). dh % 8 == 0.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void rope_scatter_kernel(const float *__restrict__ part, int splits,
@@ -180,18 +196,23 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float *__restri
     const int r = blockIdx.x;
     if (r >= counts[0]) return;
     const int b = row_seq[r], p = row_pos[r];
-    const int half = dh >> 1, slots = Hq + 2 * Hkv, n = slots * dh;
+    const int half = dh >> 1, q4 = half >> 2, slots = Hq + 2 * Hkv, n = slots * dh;
     const float *src = part + (size_t)r * n;
-    for (int e = threadIdx.x; e < slots * half; e += 256) {
-        const int hs = e / half, i = e % half;
-        float x1 = 0.f, x2 = 0.f;
+    for (int e = threadIdx.x; e < slots * q4; e += 256) {
+        const int hs = e / q4, i = (e % q4) * 4;
+        float4 x1 = make_float4(0.f, 0.f, 0.f, 0.f), x2 = x1;
+#pragma unroll 4
         for (int s = 0; s < splits; ++s) {
-            x1 += src[s * split_stride + hs * dh + i];
-            x2 += src[s * split_stride + hs * dh + i + half];
+            x1 = add4(x1, *reinterpret_cast<const float4 *>(src + s * split_stride + hs * dh + i));
+            x2 = add4(x2, *reinterpret_cast<const float4 *>(src + s * split_stride + hs * dh + i + half));
         }
         if (hs < Hq + Hkv) {
-            const float2 cs = rope[(size_t)p * half + i];
-            const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
+            const float4 c01 = *reinterpret_cast<const float4 *>(rope + (size_t)p * half + i);       // cos0 sin0 cos1 sin1
+            const float4 c23 = *reinterpret_cast<const float4 *>(rope + (size_t)p * half + i + 2);
+            const float4 y1 = make_float4(x1.x * c01.x - x2.x * c01.y, x1.y * c01.z - x2.y * c01.w,
+                                          x1.z * c23.x - x2.z * c23.y, x1.w * c23.z - x2.w * c23.w);
+            const float4 y2 = make_float4(x2.x * c01.x + x1.x * c01.y, x2.y * c01.z + x1.y * c01.w,
+                                          x2.z * c23.x + x1.z * c23.y, x2.w * c23.z + x1.w * c23.w);
             x1 = y1;
             x2 = y2;
         }
@@ -199,29 +220,31 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float *__restri
         if (hs < Hq) dst = q + ((size_t)r * Hq + hs) * dh;
         else if (hs < Hq + Hkv) dst = Kc + (((size_t)b * Hkv + (hs - Hq)) * L + p) * dh;
         else dst = Vc + (((size_t)b * Hkv + (hs - Hq - Hkv)) * L + p) * dh;
-        El<T>::st(dst + i, x1);
-        El<T>::st(dst + i + half, x2);
+        store4(dst + i, x1);
+        store4(dst + i + half, x2);
     }
 }
 
-// f[r][j] = silu(gate_j) * up_j with gate/up interleaved in the projection output.
+// f[r][j] = silu(gate_j) * up_j with gate/up interleaved in the projection output; two outputs per lane.
+__device__ __forceinline__ void store2(float *p, float a, float b) { *reinterpret_cast<float2 *>(p) = make_float2(a, b); }
+__device__ __forceinline__ void store2(bf16_t *p, float a, float b) {
+    *reinterpret_cast<uint32_t *>(p) = (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+}
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ part, int splits,
                                                      size_t split_stride, const int *__restrict__ counts,
                                                      T *__restrict__ f, int F, int fast_exp) {
     const int r = blockIdx.y;
     if (r >= counts[0]) return;
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int j = (blockIdx.x * 256 + threadIdx.x) * 2;
     if (j >= F) return;
-    const float2 *src = reinterpret_cast<const float2 *>(part + (size_t)r * 2 * F) + j;
-    float g = 0.f, u = 0.f;
-    for (int s = 0; s < splits; ++s) {
-        float2 v = *reinterpret_cast<const float2 *>(reinterpret_cast<const float *>(src) + s * split_stride);
-        g += v.x;
-        u += v.y;
-    }
-    const float sg = g / (1.0f + (fast_exp ? __expf(-g) : expf(-g)));
-    El<T>::st(f + (size_t)r * F + j, sg * u);
+    const float *src = part + (size_t)r * 2 * F + 2 * j;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);      // gate_j up_j gate_j+1 up_j+1
+#pragma unroll 4
+    for (int s = 0; s < splits; ++s) v = add4(v, *reinterpret_cast<const float4 *>(src + s * split_stride));
+    const float s0 = v.x / (1.0f + (fast_exp ? __expf(-v.x) : expf(-v.x)));
+    const float s1 = v.z / (1.0f + (fast_exp ? __expf(-v.z) : expf(-v.z)));
+    store2(f + (size_t)r * F + j, s0 * v.y, s1 * v.w);
 }
 
 // dst[c] = src[cand_row[c]] (the rows that go through the vocabulary projection)
@@ -426,10 +449,11 @@ template <typename T> int vpt_dispatch_resnorm(hipStream_t s, int rows, int d, c
 #define GO(V)                                                                                              \
     hipLaunchKernelGGL((residual_norm_kernel<T, V>), dim3(rows), dim3(256), 0, s, part, splits, stride,    \
                        counts, gain, h, a, d, eps)
-    if (d <= 256) GO(1);
-    else if (d <= 1024) GO(4);
-    else if (d <= 4096) GO(16);
-    else if (d <= 8192) GO(32);
+    if (d % 4) { dkv_set_error("d_model %d must be a multiple of 4", d); return DKV_E_UNSUPPORTED; }
+    if (d <= 1024) GO(1);
+    else if (d <= 2048) GO(2);
+    else if (d <= 4096) GO(4);
+    else if (d <= 8192) GO(8);
     else { dkv_set_error("d_model %d above 8192 is not supported", d); return DKV_E_UNSUPPORTED; }
 #undef GO
     DKV_LAUNCH_CHECK();
@@ -486,7 +510,7 @@ int dkv_launch_rope_scatter(int dtype, hipStream_t s, int rows, const float *par
 int dkv_launch_swiglu(int dtype, hipStream_t s, int rows, const float *part, int splits, size_t stride,
                       const int *counts, void *f, int F) {
     if (rows <= 0) return DKV_OK;
-    dim3 grid(ceil_div(F, 256), rows);
+    dim3 grid(ceil_div(F, 512), rows);
     if (dtype == DKV_BF16)
         hipLaunchKernelGGL((swiglu_kernel<bf16_t>), grid, dim3(256), 0, s, part, splits, stride, counts,
                            (bf16_t *)f, F, 1);

@@ -29,6 +29,36 @@ def test_projection_matches_float64_product(dtype, m, n, k):
     check_close(y, ref, 1e-5, f"gemm {m}x{n}x{k}")
 
 
+@pytest.mark.parametrize("kind,split", [("dma_32x128", 1), ("dma_32x128", 3), ("dma_64x128", 2), ("dma_128x128", 1),
+                                        ("dma_128x128", 4), ("dma_128x256", 2), ("dma_256x256", 1),
+                                        ("dma_256x256", 3), ("reg_64x128", 2)])
+@pytest.mark.parametrize("m,n,k", [(1, 128, 64), (37, 200, 192), (129, 384, 1024), (300, 520, 640), (513, 256, 2048)])
+def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
+    import paper_2505_15781_amd as P
+    if split > max(1, k // 64):
+        pytest.skip("more K slices than K tiles")
+    x = D.normal_f32(6, 1, (m, k), bf16=True)
+    w = D.normal_f32(6, 2, (n, k), std=0.02, bf16=True)
+    # the effective number of slices may be smaller than requested; ask the library's own count
+    kt = -(-k // 64)
+    kps = -(-kt // split)
+    split_eff = -(-kt // kps)
+    y = P.gemm(_dev(x, BF16), _dev(w, BF16), BF16, kind=kind, split_k=split_eff).cpu().numpy()
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    check_close(y, ref, 1e-5, f"{kind} split {split_eff} {m}x{n}x{k}")
+
+
+def test_projection_kernel_rejects_shapes_it_cannot_take():
+    import paper_2505_15781_amd as P
+    x = _dev(D.normal_f32(6, 1, (4, 72), bf16=True), BF16)
+    w = _dev(D.normal_f32(6, 2, (8, 72), bf16=True), BF16)
+    with pytest.raises(P.DkvError) as e:
+        P.gemm(x, w, BF16, kind="dma_128x128", split_k=1)      # K = 72 is not a multiple of 64
+    assert e.value.code == -3
+    y = P.gemm(x, w, BF16, kind="reg_64x128", split_k=1).cpu().numpy()
+    check_close(y, x.float().cpu().numpy().astype(np.float64) @ w.float().cpu().numpy().astype(np.float64).T, 1e-5, "reg")
+
+
 def _attn_case(shape, n_active, seed, ragged=None):
     import paper_2505_15781_amd as P
     c = D.attn_update_case(shape, n_active, seed, ragged=ragged)
