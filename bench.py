@@ -82,18 +82,21 @@ def attn_microbench(torch, P, D):
 
 
 def cpu_baseline(D, model, run, wseed, pseed):
-    """The oracle, as it stands, on a bounded sample: the first 3 denoising steps (512, 257, 256 active
-    rows) of the same configuration with the model cut to 2 of its layers; per-layer time is scaled to
+    """The oracle, as it stands, on a bounded sample: the first 6 denoising steps (512, 257 ... 253 active
+    rows) of the same configuration with the model cut to 4 of its layers; per-layer time is scaled to
     the full depth, the vocabulary head is timed in full."""
     from threadpoolctl import threadpool_info
     from oracle import sampler as SA
     from oracle import model as OM
-    small = model.with_layers(2)
+    n_small = min(4, model.n_layers)
+    small = model.with_layers(n_small)
     synth = D.SynthWeights(small, wseed)
     prompt = D.prompt_tokens(small, run, pseed)
-    synth.embed(); synth.lm_head(); synth.layer(0); synth.layer(1)      # generation is not oracle time
+    synth.embed(); synth.lm_head()
+    for l in range(n_small):
+        synth.layer(l)                                                  # generation is not oracle time
     st = SA.init_state(small, run, prompt)
-    n_steps = 3
+    n_steps = 6
     t_body = t_head = 0.0
     for t in range(n_steps):
         # time body and head separately by running the forward twice would double the cost; instead time
@@ -110,7 +113,7 @@ def cpu_baseline(D, model, run, wseed, pseed):
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": round(run.batch * run.k_per_step / per_step, 4), "unit": "tokens/s", "cores": threads,
             "kind": "oracle",
-            "sample": f"steps 0-{n_steps - 1} of the workload on a 2-layer slice, layer time x{model.n_layers // 2}, "
+            "sample": f"steps 0-{n_steps - 1} of the workload on a {n_small}-layer slice, layer time x{model.n_layers / n_small:g}, "
                       f"head in full; {t_body + t_head:.1f}s of CPU work"}
 
 

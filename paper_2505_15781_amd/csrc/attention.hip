@@ -29,6 +29,43 @@ template <int DH> struct AttnSmem {
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
+// One online-softmax step of a lane over NT sub-tiles of 16 keys (Eq. 4's softmax, streamed): st[jt][i] is the raw
+// score of key key_base + 16 jt + i against this lane's query. Updates the running max (log2 domain) and sum,
+// rescales the output accumulators, and returns the probabilities as bf16 MFMA operands: operand hh covers
+// sub-tiles 2hh and 2hh+1. The sum uses the unrounded probabilities.
+template <int NT, int NACC>
+__device__ __forceinline__ void softmax_step(f32x4 (&st)[NT], float &m_run, float &l_run, f32x4 (&acc)[NACC],
+                                             bf16x8 (&pb)[NT / 2], int key_base, int L, bool masked,
+                                             float scale_log2e) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int jt = 0; jt < NT; ++jt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (masked && key_base + 16 * jt + i >= L) st[jt][i] = -INFINITY;
+            mx = fmaxf(mx, st[jt][i]);
+        }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx * scale_log2e);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int hh = 0; hh < NT / 2; ++hh) {
+        f32x8 p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(fmaf(st[2 * hh + (e >> 2)][e & 3], scale_log2e, -m_new));
+            psum += p[e];
+        }
+        pb[hh] = __builtin_convertvector(p, bf16x8);
+    }
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int mt = 0; mt < NACC; ++mt) acc[mt] *= alpha;
+}
+
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bf16_mfma(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
@@ -152,38 +189,11 @@ __global__ __launch_bounds__(256) void attn_bf16_mfma(
             }
         }
         // st[j][i] belongs to key 16j + 4g + i and query qi
-        const int key_base = t * KT + 4 * g;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float s = st[j][i] * scale_log2e;
-                s = (key_base + 16 * j + i < L) ? s : -INFINITY;
-                st[j][i] = s;
-                mx = fmaxf(mx, s);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = exp2f(m_run - m_new);
-        m_run = m_new;
-        float psum = 0.f;
-        bf16x8 pb;
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float p = exp2f(st[j][i] - m_new);
-                // the product below sees bf16 probabilities; sum what it sees
-                bf16_t pr = f2bf(p);
-                psum += bf2f(pr);
-                pb[4 * j + i] = __builtin_bit_cast(__bf16, pr);
-            }
-        l_run = l_run * alpha + psum;
+        bf16x8 pbv[1];
+        softmax_step<2, DH / 16>(st, m_run, l_run, acc, pbv, t * KT + 4 * g, L, (t + 1) * KT > L, scale_log2e);
+        const bf16x8 pb = pbv[0];
 #pragma unroll
         for (int mt = 0; mt < DH / 16; ++mt) {
-            acc[mt] *= alpha;
             const unsigned char *vrow = vsm + (16 * mt + qi) * SM::VT_STRIDE;
             uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + g * 8);          // keys 4g..4g+3
             uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 + g * 8);     // keys 16+4g..
@@ -218,6 +228,8 @@ __global__ __launch_bounds__(256) void attn_bf16_mfma(
             *reinterpret_cast<f32x4 *>(rec + 4 + 16 * mt + 4 * g) = acc[mt];
     }
 }
+
+#include "attn_shared.h"
 
 // Merge the key slices of one (row, head): one wavefront per pair.
 template <int DH>
@@ -328,17 +340,26 @@ AttnPlan dkv_attn_plan(int dtype, int batch, int n_q_heads, int n_kv_heads, int 
                        int max_rows_per_seq) {
     AttnPlan p;
     p.use_mfma = (dtype == DKV_BF16 && (head_dim == 64 || head_dim == 128)) ? 1 : 0;
+    p.shared_nq = 0;
+    p.q_blocks = 0;
     int G = n_q_heads / n_kv_heads;
     p.q_tiles = ceil_div(max_rows_per_seq * G, 16);
     if (p.q_tiles < 1) p.q_tiles = 1;
-    int n_tiles = ceil_div(seq_len, KT);
-    long items = (long)batch * n_kv_heads * p.q_tiles;
-    int s = 1;
-    if (p.use_mfma && items < 2048) {
-        s = (int)((2048 + items - 1) / items);
-        int max_s = n_tiles / 2 > 0 ? n_tiles / 2 : 1;      // at least two tiles per slice
-        if (s > max_s) s = max_s;
+    int s = 1, n_tiles;
+    if (p.use_mfma && head_dim == 128 && p.q_tiles >= 4) {
+        // enough query rows to give every wavefront of a workgroup its own tile(s)
+        p.shared_nq = p.q_tiles >= 8 ? 2 : 1;
+        p.q_blocks = ceil_div(p.q_tiles, 4 * p.shared_nq);
+        n_tiles = ceil_div(seq_len, 64);
+        long items = (long)batch * n_kv_heads * p.q_blocks;
+        if (items < 512) s = (int)((512 + items - 1) / items);
+    } else {
+        n_tiles = ceil_div(seq_len, KT);
+        long items = (long)batch * n_kv_heads * p.q_tiles;
+        if (p.use_mfma && items < 2048) s = (int)((2048 + items - 1) / items);
     }
+    int max_s = n_tiles / 2 > 0 ? n_tiles / 2 : 1;      // at least two tiles per slice
+    if (s > max_s) s = max_s;
     p.tiles_per_split = ceil_div(n_tiles, s);
     p.splits = ceil_div(n_tiles, p.tiles_per_split);
     return p;
@@ -368,7 +389,39 @@ int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const vo
     dim3 grid((unsigned)((items + 3) / 4));
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
     long pairs = (long)rows_upper * n_q_heads;
-    if (head_dim == 128) {
+    if (plan.shared_nq) {
+        const size_t smem = 2 * (64 * (128 * 2 + 16) + 128 * (64 * 2 + 8));
+        const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_blocks * plan.splits);
+        static bool lds_ok1 = false, lds_ok2 = false;
+        if (plan.shared_nq == 1) {
+            if (!lds_ok1) {
+                DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                lds_ok1 = true;
+            }
+            hipLaunchKernelGGL((attn_bf16_shared<1>), dim3(wgs), dim3(256), smem, stream, (const bf16_t *)q,
+                               (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out,
+                               (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits,
+                               plan.tiles_per_split, rows_upper, scale_log2e);
+        } else {
+            if (!lds_ok2) {
+                DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                lds_ok2 = true;
+            }
+            hipLaunchKernelGGL((attn_bf16_shared<2>), dim3(wgs), dim3(256), smem, stream, (const bf16_t *)q,
+                               (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out,
+                               (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits,
+                               plan.tiles_per_split, rows_upper, scale_log2e);
+        }
+        DKV_LAUNCH_CHECK();
+        if (plan.splits > 1) {
+            hipLaunchKernelGGL((attn_merge<128>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream,
+                               (const float *)partial, (bf16_t *)out, row_off, batch, n_q_heads, plan.splits,
+                               rows_upper);
+            DKV_LAUNCH_CHECK();
+        }
+    } else if (head_dim == 128) {
         size_t smem = 4 * AttnSmem<128>::WAVE_BYTES;
         static bool lds_ok = false;
         if (!lds_ok) {

@@ -1,0 +1,182 @@
+// Attention kernel for larger active sets: the four wavefronts of a workgroup share each K/V tile.
+// Included by attention.hip (uses its helpers); head_dim 128 only.
+//
+// Work item = (sequence, kv head, block of 4*NQ query tiles of 16 rows, key slice). The workgroup
+// streams its key slice in tiles of 64 keys: every thread fetches part of the K rows and of the V rows
+// (the latter transposed on the way into LDS), two LDS stages alternate, and the next tile's global
+// loads are in flight while the current one is multiplied. Each wavefront multiplies its own NQ query
+// tiles against the shared tile, so a K or V fragment read from LDS feeds NQ MFMAs and the tile is read
+// from L2 once per 64*NQ query rows instead of once per 16.
+#pragma once
+
+template <int NQ>
+__global__ __launch_bounds__(256) void attn_bf16_shared(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
+    const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
+    int Hq, int Hkv, int L, int q_blocks, int splits, int tiles_per_split, int rows_cap,
+    float scale_log2e) {
+    constexpr int DH = 128, KT2 = 64;
+    constexpr int K_STRIDE = DH * 2 + 16;      // bytes per key row
+    constexpr int VT_STRIDE = KT2 * 2 + 8;     // bytes per head-dim row of V^T
+    constexpr int K_BYTES = KT2 * K_STRIDE, STAGE_BYTES = K_BYTES + DH * VT_STRIDE;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = Hq / Hkv;
+    long item = blockIdx.x;
+    const int split = (int)(item % splits); item /= splits;
+    const int qb = (int)(item % q_blocks);  item /= q_blocks;
+    const int kvh = (int)(item % Hkv);
+    const int b = (int)(item / Hkv);
+    if (b >= batch) return;
+
+    const int r0 = row_off[b], nrows = row_off[b + 1] - r0;
+    const int nq = nrows * G;
+    const int mb0 = qb * 4 * NQ * 16;
+    if (mb0 >= nq) return;                       // uniform for the workgroup
+
+    const int qi = lane & 15, g = lane >> 4;
+    bool q_ok[NQ];
+    int q_row[NQ], q_head[NQ];
+    bf16x8 qf[NQ][DH / 32];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const int mq = mb0 + (wave * NQ + j) * 16 + qi;
+        q_ok[j] = mq < nq && r0 + mq / G < rows_cap;
+        q_row[j] = q_ok[j] ? r0 + mq / G : 0;
+        q_head[j] = kvh * G + (q_ok[j] ? mq % G : 0);
+        const bf16_t *qp = Q + ((size_t)q_row[j] * Hq + q_head[j]) * DH + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < DH / 32; ++ks) {
+            uint4 v = q_ok[j] ? *reinterpret_cast<const uint4 *>(qp + 32 * ks) : make_uint4(0, 0, 0, 0);
+            qf[j][ks] = *reinterpret_cast<bf16x8 *>(&v);
+        }
+    }
+
+    const bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    const bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    const int n_tiles = (L + KT2 - 1) / KT2;
+    const int t0 = split * tiles_per_split, t1 = min(n_tiles, t0 + tiles_per_split);
+
+    // per thread: 4 K chunks (16 B) and one 4-key x 8-dim block of V
+    uint4 kreg[4], vreg[4];
+    const int v_dc = tid & 15, v_kg = tid >> 4;
+    auto load_tile = [&](int t) {
+        const int key0 = t * KT2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + 256 * i, key = c >> 4, ch = c & 15, gk = key0 + key;
+            kreg[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gk = key0 + 4 * v_kg + j;
+            vreg[j] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + v_dc * 8) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_tile = [&](int stage) {
+        unsigned char *ksm = smem_raw + stage * STAGE_BYTES, *vsm = ksm + K_BYTES;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + 256 * i, key = c >> 4, ch = c & 15;
+            *reinterpret_cast<uint4 *>(ksm + key * K_STRIDE + ch * 16) = kreg[i];
+        }
+        const uint32_t *v0 = reinterpret_cast<const uint32_t *>(&vreg[0]);
+        const uint32_t *v1 = reinterpret_cast<const uint32_t *>(&vreg[1]);
+        const uint32_t *v2 = reinterpret_cast<const uint32_t *>(&vreg[2]);
+        const uint32_t *v3 = reinterpret_cast<const uint32_t *>(&vreg[3]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {      // word e holds dims 2e (low half) and 2e+1 (high half)
+            const uint2 lo = make_uint2(pack_lo(v0[e], v1[e]), pack_lo(v2[e], v3[e]));
+            const uint2 hi = make_uint2(pack_hi(v0[e], v1[e]), pack_hi(v2[e], v3[e]));
+            const int d = v_dc * 8 + 2 * e;
+            *reinterpret_cast<uint2 *>(vsm + d * VT_STRIDE + v_kg * 8) = lo;
+            *reinterpret_cast<uint2 *>(vsm + (d + 1) * VT_STRIDE + v_kg * 8) = hi;
+        }
+    };
+
+    float m_run[NQ], l_run[NQ];
+    f32x4 acc[NQ][DH / 16];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        m_run[j] = -INFINITY;
+        l_run[j] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DH / 16; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    if (t0 < t1) {
+        load_tile(t0);
+        store_tile(0);
+    }
+    __syncthreads();
+    for (int t = t0; t < t1; ++t) {
+        const int stage = (t - t0) & 1;
+        if (t + 1 < t1) load_tile(t + 1);
+        const unsigned char *ksm = smem_raw + stage * STAGE_BYTES, *vsm = ksm + K_BYTES;
+        f32x4 st[NQ][4];
+#pragma unroll
+        for (int j = 0; j < NQ; ++j)
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) st[j][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            const unsigned char *krow = ksm + (16 * jt + qi) * K_STRIDE + g * 16;
+#pragma unroll
+            for (int ks = 0; ks < DH / 32; ++ks) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(krow + ks * 64);
+#pragma unroll
+                for (int j = 0; j < NQ; ++j)
+                    st[j][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[j][ks], st[j][jt], 0, 0, 0);
+            }
+        }
+        // st[j][jt][i] is the score of key 16 jt + 4g + i of this tile against query qi of tile j
+        bf16x8 pb[NQ][2];
+#pragma unroll
+        for (int j = 0; j < NQ; ++j)
+            softmax_step<4, DH / 16>(st[j], m_run[j], l_run[j], acc[j], pb[j], t * KT2 + 4 * g, L, (t + 1) * KT2 > L,
+                                     scale_log2e);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int mt = 0; mt < DH / 16; ++mt) {
+                const unsigned char *vrow = vsm + (16 * mt + qi) * VT_STRIDE + 64 * hh;
+                const uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + g * 8);          // keys 4g..4g+3
+                const uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 + g * 8);     // keys 16+4g..
+                uint4 av = make_uint4(a0.x, a0.y, a1.x, a1.y);
+#pragma unroll
+                for (int j = 0; j < NQ; ++j)
+                    acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&av), pb[j][hh],
+                                                                         acc[j][mt], 0, 0, 0);
+            }
+        if (t + 1 < t1) store_tile(stage ^ 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        float l = l_run[j];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        if (!q_ok[j]) continue;
+        if (splits == 1) {
+            const float inv = 1.f / l;
+            bf16_t *op = out + ((size_t)q_row[j] * Hq + q_head[j]) * DH;
+#pragma unroll
+            for (int mt = 0; mt < DH / 16; ++mt) {
+                uint2 w;
+                w.x = (uint32_t)f2bf(acc[j][mt][0] * inv) | ((uint32_t)f2bf(acc[j][mt][1] * inv) << 16);
+                w.y = (uint32_t)f2bf(acc[j][mt][2] * inv) | ((uint32_t)f2bf(acc[j][mt][3] * inv) << 16);
+                *reinterpret_cast<uint2 *>(op + 16 * mt + 4 * g) = w;
+            }
+        } else {
+            float *rec = part + (((size_t)q_row[j] * Hq + q_head[j]) * splits + split) * (DH + 4);
+            if (g == 0) {
+                rec[0] = m_run[j];
+                rec[1] = l;
+            }
+#pragma unroll
+            for (int mt = 0; mt < DH / 16; ++mt) *reinterpret_cast<f32x4 *>(rec + 4 + 16 * mt + 4 * g) = acc[j][mt];
+        }
+    }
+}

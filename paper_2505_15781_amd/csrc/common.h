@@ -11,6 +11,7 @@ typedef uint16_t bf16_t;   // raw bfloat16 bits
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) float f32x8;
 
 #define DKV_WAVE 64
 
@@ -30,13 +31,8 @@ void dkv_set_error(const char *fmt, ...);
 
 __device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ bf16_t f2bf(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
-}
+// round to nearest even (the hardware conversion); NaN stays NaN
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 
 template <typename T> struct El;
 template <> struct El<float> {
@@ -95,7 +91,9 @@ struct AttnPlan {
     int use_mfma;     // 1: bf16 MFMA kernel, 0: generic kernel
     int q_tiles;      // 16-row query tiles per (sequence, kv head), upper bound
     int splits;       // slices of the key range
-    int tiles_per_split;
+    int tiles_per_split;   // in tiles of 32 keys (wave-private kernel) or 64 keys (shared kernel)
+    int shared_nq;    // 0: one wavefront per item; 1 or 2: workgroup-shared K/V tiles, query tiles per wavefront
+    int q_blocks;     // shared kernel: blocks of 4 * shared_nq query tiles
 };
 AttnPlan dkv_attn_plan(int dtype, int batch, int n_q_heads, int n_kv_heads, int seq_len, int head_dim,
                        int max_rows_per_seq);
