@@ -1,0 +1,73 @@
+"""Microbenchmark of the projection kernel on the layer shapes of a model configuration.
+
+Runs y = x W^T through the library (`dkv_gemm`, heuristic kernel choice) for the four projections of
+one transformer layer at a sample of the row counts a dKV-Cache-Decode schedule produces, rotating
+over enough weight buffers that every launch streams its weights from HBM. Used on its own for
+kernel timing and under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` for HBM traffic per launch
+(`--copy-calibration` adds one elementwise kernel that reads and writes exactly 1 GiB).
+
+    python -m paper_2505_15781_amd.kernel_bench --config 2 --rows 2,32,64,128,192,256,512
+"""
+import argparse
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))   # runnable as a script from any cwd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4])
+    ap.add_argument("--rows", default="2,32,64,128,192,256,512")
+    ap.add_argument("--reps", type=int, default=4)
+    ap.add_argument("--copy-calibration", action="store_true")
+    args = ap.parse_args()
+    import torch
+    import dkv_inputs as D
+    from paper_2505_15781_amd import binding
+    from paper_2505_15781_amd.binding import lib, _ptr, _stream, _check
+
+    model = D.model_run(args.config)[0]
+    d, F = model.d_model, model.d_ffn
+    shapes = {"qkv": (model.qkv_rows, d), "o": (d, model.n_q_heads * model.head_dim), "gate_up": (2 * F, d),
+              "down": (d, F)}
+    torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+    g = torch.Generator(device="cuda").manual_seed(1)
+    for name, (N, K) in shapes.items():
+        nbuf = max(2, int(600e6 // (N * K * 2)) + 1)
+        Ws = [(torch.randn(N, K, generator=g, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(nbuf)]
+        for M in [int(r) for r in args.rows.split(",")]:
+            x = torch.randn(M, K, generator=g, device="cuda").to(torch.bfloat16)
+            y = torch.empty(M, N, device="cuda", dtype=torch.float32)
+            nb = lib.dkv_gemm_workspace_bytes(M, N, K, binding.BF16)
+            ws = torch.empty(max(nb, 4), dtype=torch.uint8, device="cuda")
+
+            def run(w):
+                _check(lib.dkv_gemm(_ptr(x), _ptr(w), _ptr(y), M, N, K, binding.BF16, _ptr(ws), nb, _stream()))
+
+            for w in Ws:
+                run(w)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.reps):
+                for w in Ws:
+                    run(w)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (args.reps * nbuf)
+            nbytes = (M * K + N * K) * 2 + 4 * M * N
+            print(f"{name:8s} M={M:5d} N={N:6d} K={K:6d} k_slices={max(1, nb // (4 * M * N))} {us:8.1f} us "
+                  f"{nbytes / us * 1e-3:7.0f} GB/s {2.0 * M * N * K / us * 1e-6:7.1f} TFLOP/s", flush=True)
+        del Ws
+        torch.cuda.empty_cache()
+
+
+if __name__ == "__main__":
+    sys.exit(main())
