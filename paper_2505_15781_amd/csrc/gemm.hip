@@ -316,20 +316,35 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
         p.kind = GEMM_REG_64x128;
         return p;
     }
-    const bool wide = n >= 8192;
-    if (m_upper <= 32) p.kind = GEMM_DMA_32x128;
-    else if (m_upper <= 64) p.kind = GEMM_DMA_64x128;
-    else if (m_upper <= 128) p.kind = GEMM_DMA_128x128;
-    else if (!wide) p.kind = m_upper >= 1024 ? GEMM_DMA_256x256 : GEMM_DMA_128x128;
-    else if (m_upper <= 384) p.kind = GEMM_DMA_128x256;
-    else p.kind = GEMM_DMA_256x256;
+    // Tile shape and K split from a sweep of every (kernel, split) pair over the LLaDA-8B layer shapes at row
+    // counts 16..512 on MI355X. Wide outputs (QKV, gate/up) have enough column tiles to fill the chip alone and
+    // take the largest tile the row count uses fully; narrow outputs (O, down: N = d_model) keep tiles small
+    // and split K instead, more so when K is long.
+    const bool wide = n >= 8192, very_wide = n >= 16384, long_k = k >= 8192;
+    if (wide) {
+        if (m_upper <= 32) p.kind = GEMM_DMA_32x128;
+        else if (m_upper <= 64) p.kind = GEMM_DMA_64x128;
+        else if (m_upper <= 128) p.kind = GEMM_DMA_128x128;
+        else if (m_upper <= 256) p.kind = very_wide ? GEMM_DMA_128x256 : GEMM_DMA_128x128;
+        else if (m_upper <= 768) p.kind = very_wide ? GEMM_DMA_256x256 : GEMM_DMA_128x256;
+        else p.kind = GEMM_DMA_256x256;
+    } else {
+        if (m_upper <= 32) p.kind = GEMM_DMA_32x128;
+        else if (m_upper <= 64) p.kind = long_k ? GEMM_DMA_64x128 : GEMM_DMA_32x128;
+        else if (m_upper <= 256) p.kind = long_k ? GEMM_DMA_128x128 : GEMM_DMA_64x128;
+        else if (m_upper <= 768) p.kind = long_k ? GEMM_DMA_128x256 : GEMM_DMA_128x128;
+        else if (m_upper <= 2048) p.kind = GEMM_DMA_128x256;
+        else p.kind = GEMM_DMA_256x256;
+    }
     const KindInfo &ki = kKinds[p.kind];
     const int tiles = ceil_div(m_upper, ki.bm) * ceil_div(n, ki.bn);
-    int s = 320 / tiles;
+    int s = 256 / tiles;
     const int kt_total = k / BK;
     const int max_s = kt_total / 8 > 0 ? kt_total / 8 : 1;      // at least 8 K tiles per slice
     if (s > 8) s = 8;
     if (s > max_s) s = max_s;
+    if (s == 5) s = 4;                                          // uneven slices cost more than they fill
+    if (s == 7) s = 6;
     if (s < 1) s = 1;
     p.split_k = effective_split(k, s);
     return p;
