@@ -294,7 +294,8 @@ def gemm(x, w, dtype, kind=None, split_k=1):
         ws = torch.empty(max(nb, 4), dtype=torch.uint8, device=x.device)
         _check(lib.dkv_gemm(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, _ptr(ws), nb, _stream()))
     else:
-        nb = split_k * m * n * 4 if split_k > 1 else 0
+        slots = 2 if split_k < 0 else split_k          # split_k = -1: the 3/4-share mode, two partial slots
+        nb = slots * m * n * 4 if slots > 1 else 0
         ws = torch.empty(max(nb, 4), dtype=torch.uint8, device=x.device)
         _check(lib.dkv_gemm_with(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, GEMM_KINDS[kind], split_k, _ptr(ws),
                                  nb, _stream()))

@@ -577,7 +577,8 @@ extern "C" int dkv_gemm_with(const void *x, const void *w, float *y, int32_t m, 
     if (dtype != DKV_BF16 && dtype != DKV_FP32) { dkv_set_error("unknown dtype"); return DKV_E_INVALID_ARG; }
     GemmPlan p;
     p.kind = kind;
-    p.split_k = split_k;
+    p.split_k = split_k < 0 ? 2 : split_k;
+    p.frac_units = split_k < 0 ? (k / 64) * 3 / 4 : 0;      // split_k = -1 asks for the 3/4 share
     if (!dkv_gemm_plan_valid(dtype, k, p)) {
         dkv_set_error("kernel %d with %d K slices does not take dtype %d, K %d", kind, split_k, dtype, k);
         return DKV_E_UNSUPPORTED;

@@ -77,7 +77,8 @@ enum { GEMM_DMA_32x128 = 0, GEMM_DMA_64x128, GEMM_DMA_128x128, GEMM_DMA_128x256,
        GEMM_REG_64x128, GEMM_SIMT, GEMM_KINDS };
 struct GemmPlan {
     int kind;      // GEMM_* kernel and tile shape
-    int split_k;   // number of K slices; slice s writes partial[s]
+    int split_k;   // number of partial slots: slice or part s writes partial[s]
+    int frac_units; // 0, or K tiles per workgroup when workgroups take 3/4 of a tile's K range each
 };
 GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k);
 int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p);

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
                                                          const bf16_t *__restrict__ W, float *__restrict__ P,
                                                          int m_upper, int m_cap,
                                                          const int *__restrict__ m_dev, int N, int K,
-                                                         int kt_per_split) {
+                                                         int kt_per_split, int frac_units) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN, NW = WM * WN;
     constexpr int CA = BM / (8 * NW), CW = BN / (8 * NW);     // load instructions per thread per tile
     constexpr int STAGE_CHUNKS = (BM + BN) * 8;
@@ -44,15 +44,38 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
 
     const int M = m_dev ? min(*m_dev, m_upper) : m_upper;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    if (m0 >= M) return;
     const int kt_total = K / BK;
-    const int kt0 = blockIdx.z * kt_per_split;
-    const int nk = min(kt_total, kt0 + kt_per_split) - kt0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds_base = (uint32_t)(size_t)(lds_ptr_t)lds;
+
+    // Work of this workgroup: one (tile, K slice) given by the 3-D grid, or, in fractional mode, the K-tile
+    // units [w u, (w+1) u) of the sequence "tile 0's K tiles, tile 1's K tiles, ..." (tiles column-fastest),
+    // which may end one output tile and begin the next. The part of tile t done by workgroup w goes to
+    // partial slot w - floor(t * kt_total / u); the host only uses shares for which every tile gets the same
+    // number of parts.
+    const int tiles_n = (N + BN - 1) / BN;
+    int unit = frac_units ? blockIdx.x * frac_units : 0;
+    const int unit_end = frac_units ? min(unit + frac_units, tiles_n * ((m_upper + BM - 1) / BM) * kt_total) : 0;
+  for (;;) {
+    int m0, n0, kt0, nk, slot;
+    if (frac_units) {
+        const int tile = unit / kt_total;
+        kt0 = unit - tile * kt_total;
+        nk = min(kt_total - kt0, unit_end - unit);
+        m0 = (tile / tiles_n) * BM;
+        n0 = (tile % tiles_n) * BN;
+        slot = blockIdx.x - (tile * kt_total) / frac_units;
+        unit += nk;
+    } else {
+        m0 = blockIdx.y * BM;
+        n0 = blockIdx.x * BN;
+        kt0 = blockIdx.z * kt_per_split;
+        nk = min(kt_total, kt0 + kt_per_split) - kt0;
+        slot = blockIdx.z;
+    }
+    if (m0 < M) {
 
     // Source pointer of each load instruction for K tile kt0. Slot s of a stage holds row s/8, and in
     // position s%8 the chunk (s%8) ^ ((row>>1)&7). Rows past the end are clamped: they only feed outputs
@@ -130,9 +153,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], wf[ks & 1][j], acc[i][j], 0, 0, 0);
         }
     }
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));   // the clamped tail loads must land before LDS is released
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));   // the clamped tail loads must land before LDS is reused
 
-    float *out = P + (size_t)blockIdx.z * m_cap * N;
+    float *out = P + (size_t)slot * m_cap * N;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -144,6 +167,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
                 if (m < M && n < N) out[(size_t)m * N + n] = acc[i][j][v];
             }
         }
+    }   // m0 < M
+    if (!frac_units || unit >= unit_end) break;
+    __syncthreads();      // every wave is done with the LDS stages before the next part refills them
+  }
 }
 
 // Register-staged variant for K that is a multiple of 8 but not of 64 (zero-fills the K tail).
@@ -280,7 +307,7 @@ constexpr KindInfo kKinds[] = {
 
 template <int MT, int NT, int WM, int WN, int STAGES>
 int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, const int *m_dev, int n, int k,
-               int split, hipStream_t s) {
+               int split, int frac_units, hipStream_t s) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
     constexpr int smem = STAGES * (BM + BN) * 128;
     static bool attr_set = false;
@@ -291,8 +318,9 @@ int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, c
     }
     const int kt_total = k / BK, kps = ceil_div(kt_total, split);
     dim3 grid(ceil_div(n, BN), ceil_div(m_upper, BM), ceil_div(kt_total, kps));
+    if (frac_units) grid = dim3(ceil_div(grid.x * grid.y * kt_total, frac_units), 1, 1);
     hipLaunchKernelGGL((gemm_dma<MT, NT, WM, WN, STAGES>), grid, dim3(64 * WM * WN), smem, s, (const bf16_t *)A,
-                       (const bf16_t *)W, P, m_upper, m_cap, m_dev, n, k, kps);
+                       (const bf16_t *)W, P, m_upper, m_cap, m_dev, n, k, kps, frac_units);
     DKV_LAUNCH_CHECK();
     return DKV_OK;
 }
@@ -308,6 +336,7 @@ int effective_split(int k, int split) {
 GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     GemmPlan p;
     p.split_k = 1;
+    p.frac_units = 0;
     if (dtype != DKV_BF16 || (k % 8) != 0) {
         p.kind = GEMM_SIMT;
         return p;
@@ -347,11 +376,19 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     if (s == 7) s = 6;
     if (s < 1) s = 1;
     p.split_k = effective_split(k, s);
+    // Shapes with 192 tiles leave a quarter of the 256 compute units idle. Giving 256 workgroups 3/4 of a
+    // tile's K range each (frac_units, kept for experiments through dkv_gemm_with) fills the chip but was
+    // measured to take the same time: those launches are bound by total L2-to-LDS traffic, not per unit.
     return p;
 }
 
 int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p) {
-    if (p.split_k < 1 || p.kind < 0 || p.kind >= GEMM_KINDS) return 0;
+    if (p.split_k < 1 || p.kind < 0 || p.kind >= GEMM_KINDS || p.frac_units < 0) return 0;
+    if (p.frac_units) {
+        // a 3/4 share: every tile is covered by exactly two workgroups
+        if (p.kind > GEMM_DMA_256x256 || dtype != DKV_BF16 || (k % BK) != 0) return 0;
+        return p.split_k == 2 && (k / BK) % 4 == 0 && p.frac_units == (k / BK) * 3 / 4;
+    }
     if (p.kind == GEMM_SIMT) return p.split_k == 1;
     if (dtype != DKV_BF16 || (k % 8) != 0) return 0;
     if (p.kind != GEMM_REG_64x128 && (k % BK) != 0) return 0;
@@ -367,15 +404,15 @@ int dkv_launch_gemm(int dtype, const void *A, const void *W, float *partial, int
     }
     switch (p.kind) {
         case GEMM_DMA_32x128:
-            return launch_dma<1, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+            return launch_dma<1, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
         case GEMM_DMA_64x128:
-            return launch_dma<2, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+            return launch_dma<2, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
         case GEMM_DMA_128x128:
-            return launch_dma<2, 2, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+            return launch_dma<2, 2, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
         case GEMM_DMA_128x256:
-            return launch_dma<2, 4, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+            return launch_dma<2, 4, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
         case GEMM_DMA_256x256:
-            return launch_dma<4, 4, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, stream);
+            return launch_dma<4, 4, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
         case GEMM_REG_64x128: {
             const int kt_total = ceil_div(k, BK), kps = ceil_div(kt_total, p.split_k);
             dim3 grid(ceil_div(n, 128), ceil_div(m_upper, 64), p.split_k);

@@ -48,6 +48,17 @@ def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
     check_close(y, ref, 1e-5, f"{kind} split {split_eff} {m}x{n}x{k}")
 
 
+@pytest.mark.parametrize("kind", ["dma_32x128", "dma_64x128", "dma_128x128", "dma_128x256", "dma_256x256"])
+@pytest.mark.parametrize("m,n,k", [(5, 128, 256), (37, 200, 512), (129, 384, 1024), (300, 520, 768), (257, 1536, 4096)])
+def test_three_quarter_k_share_covers_every_tile_twice(kind, m, n, k):
+    """Workgroups that take 3/4 of a tile's K range each (possibly ending one tile and starting the next)."""
+    import paper_2505_15781_amd as P
+    x = D.normal_f32(8, 1, (m, k), bf16=True)
+    w = D.normal_f32(8, 2, (n, k), std=0.02, bf16=True)
+    y = P.gemm(_dev(x, BF16), _dev(w, BF16), BF16, kind=kind, split_k=-1).cpu().numpy()
+    check_close(y, x.astype(np.float64) @ w.astype(np.float64).T, 1e-5, f"{kind} 3/4 share {m}x{n}x{k}")
+
+
 def test_projection_kernel_rejects_shapes_it_cannot_take():
     import paper_2505_15781_amd as P
     x = _dev(D.normal_f32(6, 1, (4, 72), bf16=True), BF16)
