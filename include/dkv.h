@@ -183,10 +183,12 @@ int dkv_destroy(dkv_ctx *ctx);
 #define DKV_GEMM_DMA_128x128  2
 #define DKV_GEMM_DMA_128x256  3
 #define DKV_GEMM_DMA_256x256  4
-#define DKV_GEMM_REG_64x128   5   /* bf16 with K not a multiple of 64 */
-#define DKV_GEMM_SIMT         6   /* fp32 mode / generic */
-#define DKV_PROF_ATTN         7   /* attention (including the key-slice merge when it runs) */
-#define DKV_PROF_KINDS        8
+#define DKV_GEMM_DMA_128x96   5
+#define DKV_GEMM_DMA_128x192  6
+#define DKV_GEMM_REG_64x128   7   /* bf16 with K not a multiple of 64 */
+#define DKV_GEMM_SIMT         8   /* fp32 mode / generic */
+#define DKV_PROF_ATTN         9   /* attention (including the key-slice merge when it runs) */
+#define DKV_PROF_KINDS        10
 typedef struct {
     int64_t launches;
     double ms, bytes, flops;
@@ -222,11 +224,15 @@ int dkv_attn_update(void *k_cache, void *v_cache, const void *q, const void *k_n
 size_t dkv_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t dtype);
 int dkv_gemm(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k,
              int32_t dtype, void *workspace, size_t workspace_bytes, void *stream);
-/* The same with the kernel (DKV_GEMM_*) and the number of K slices chosen by the caller instead of the
- * library's heuristic, so every kernel can be checked on every shape. workspace must hold
- * split_k * m * n floats when split_k > 1. DKV_E_UNSUPPORTED if the kernel does not take the shape. */
+/* The same with the kernel (DKV_GEMM_*), the number of K slices and the launch options chosen by the
+ * caller instead of the library's heuristic, so every kernel can be checked on every shape. workspace
+ * must hold split_k * m * n floats when split_k > 1. `options` is a sum of DKV_GEMM_OPT_* (ignored by
+ * the kernels that have no such option, and dropped when the grid does not fit them).
+ * DKV_E_UNSUPPORTED if the kernel does not take the shape, DKV_E_INVALID_ARG for unknown option bits. */
+#define DKV_GEMM_OPT_STAGGER    1   /* every workgroup starts its K loop at a different K tile */
+#define DKV_GEMM_OPT_XCD_GROUP  2   /* workgroups that share an XCD's L2 take neighbouring tiles */
 int dkv_gemm_with(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k,
-                  int32_t dtype, int32_t kind, int32_t split_k, void *workspace,
+                  int32_t dtype, int32_t kind, int32_t split_k, int32_t options, void *workspace,
                   size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus

@@ -61,9 +61,10 @@ class ProfEntry(C.Structure):
 
 
 PROF_KINDS = ("gemm_dma<1,1,1,4,4>", "gemm_dma<2,1,1,4,4>", "gemm_dma<2,2,2,2,3>", "gemm_dma<2,4,2,2,3>",
-              "gemm_dma<4,4,2,2,2>", "gemm_reg", "gemm_simt", "attention")
+              "gemm_dma<4,4,2,2,2>", "gemm_dma<1,3,4,1,4>", "gemm_dma<2,3,2,2,3>", "gemm_reg", "gemm_simt",
+              "attention")
 GEMM_KINDS = {"dma_32x128": 0, "dma_64x128": 1, "dma_128x128": 2, "dma_128x256": 3, "dma_256x256": 4,
-              "reg_64x128": 5, "simt": 6}
+              "dma_128x96": 5, "dma_128x192": 6, "reg_64x128": 7, "simt": 8}
 lib.dkv_profile_begin.argtypes = [c_vp]
 lib.dkv_profile_end.argtypes = [c_vp, C.POINTER(ProfEntry)]
 lib.dkv_attn_update_workspace_bytes.restype = c_sz
@@ -72,7 +73,7 @@ lib.dkv_attn_update.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp, c_sz, c_vp]
 lib.dkv_gemm_workspace_bytes.restype = c_sz
 lib.dkv_gemm_workspace_bytes.argtypes = [c_i32] * 4
 lib.dkv_gemm.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_sz, c_vp]
-lib.dkv_gemm_with.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_vp, c_sz, c_vp]
+lib.dkv_gemm_with.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_vp, c_sz, c_vp]
 
 
 class DkvError(RuntimeError):
@@ -284,7 +285,10 @@ def attn_update(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, 
                                _stream()))
 
 
-def gemm(x, w, dtype, kind=None, split_k=1):
+GEMM_OPT_STAGGER, GEMM_OPT_XCD_GROUP = 1, 2
+
+
+def gemm(x, w, dtype, kind=None, split_k=1, options=0):
     """y = x @ w.T in fp32 through the library's projection kernel (heuristic choice unless `kind`)."""
     m, k = x.shape
     n = w.shape[0]
@@ -297,6 +301,6 @@ def gemm(x, w, dtype, kind=None, split_k=1):
         slots = 2 if split_k < 0 else split_k          # split_k = -1: the 3/4-share mode, two partial slots
         nb = slots * m * n * 4 if slots > 1 else 0
         ws = torch.empty(max(nb, 4), dtype=torch.uint8, device=x.device)
-        _check(lib.dkv_gemm_with(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, GEMM_KINDS[kind], split_k, _ptr(ws),
-                                 nb, _stream()))
+        _check(lib.dkv_gemm_with(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, GEMM_KINDS[kind], split_k, options,
+                                 _ptr(ws), nb, _stream()))
     return y

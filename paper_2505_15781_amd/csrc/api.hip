@@ -572,13 +572,20 @@ extern "C" size_t dkv_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int3
 }
 
 extern "C" int dkv_gemm_with(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k, int32_t dtype,
-                             int32_t kind, int32_t split_k, void *workspace, size_t workspace_bytes, void *stream) {
+                             int32_t kind, int32_t split_k, int32_t options, void *workspace,
+                             size_t workspace_bytes, void *stream) {
     if (!x || !w || !y || m < 1 || n < 1 || k < 1) { dkv_set_error("bad argument"); return DKV_E_INVALID_ARG; }
+    if (options & ~(DKV_GEMM_OPT_STAGGER | DKV_GEMM_OPT_XCD_GROUP)) {
+        dkv_set_error("unknown projection option bits 0x%x", options);
+        return DKV_E_INVALID_ARG;
+    }
     if (dtype != DKV_BF16 && dtype != DKV_FP32) { dkv_set_error("unknown dtype"); return DKV_E_INVALID_ARG; }
     GemmPlan p;
     p.kind = kind;
     p.split_k = split_k < 0 ? 2 : split_k;
     p.frac_units = split_k < 0 ? (k / 64) * 3 / 4 : 0;      // split_k = -1 asks for the 3/4 share
+    p.flags = ((options & DKV_GEMM_OPT_STAGGER) ? GEMM_FLAG_STAGGER : 0) |
+              ((options & DKV_GEMM_OPT_XCD_GROUP) ? GEMM_FLAG_XCD_GROUP : 0);
     if (!dkv_gemm_plan_valid(dtype, k, p)) {
         dkv_set_error("kernel %d with %d K slices does not take dtype %d, K %d", kind, split_k, dtype, k);
         return DKV_E_UNSUPPORTED;
@@ -600,5 +607,7 @@ extern "C" int dkv_gemm(const void *x, const void *w, float *y, int32_t m, int32
                         void *workspace, size_t workspace_bytes, void *stream) {
     if (m < 1 || n < 1 || k < 1) { dkv_set_error("bad argument"); return DKV_E_INVALID_ARG; }
     GemmPlan p = dkv_gemm_plan(dtype, m, n, k);
-    return dkv_gemm_with(x, w, y, m, n, k, dtype, p.kind, p.split_k, workspace, workspace_bytes, stream);
+    const int options = ((p.flags & GEMM_FLAG_STAGGER) ? DKV_GEMM_OPT_STAGGER : 0) |
+                        ((p.flags & GEMM_FLAG_XCD_GROUP) ? DKV_GEMM_OPT_XCD_GROUP : 0);
+    return dkv_gemm_with(x, w, y, m, n, k, dtype, p.kind, p.split_k, options, workspace, workspace_bytes, stream);
 }

@@ -12,6 +12,11 @@
 // boundaries. Measured on MI355X a compute unit sustains about 60 GB/s of such fills whatever the depth,
 // so the tile shapes below are chosen to keep the bytes each workgroup pulls (W tile + A tile) small
 // relative to its MFMA work, and K is split across workgroups only as far as needed to fill 256 CUs.
+// Two launch options, both measured: `stagger` starts each workgroup's K loop at a different tile (unsplit
+// launches otherwise sweep the same columns of A and W in step and crowd a few memory channels: up to 25 %
+// on the widest projection at <= 128 rows); `xcd_group` renumbers workgroups so that the 32 that run
+// together on one XCD (hardware sends workgroup i to XCD i mod 8) cover a compact 4 x 8 block of tiles and
+// share their A and W tiles through that XCD's L2 (hit rate 54 % -> 78 % and 5 % less time at 6144 rows).
 // bf16, other K (multiple of 8): `gemm_reg`, register-staged tiles. fp32 mode / anything else: `gemm_simt`.
 #include "common.h"
 
@@ -36,9 +41,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
                                                          const bf16_t *__restrict__ W, float *__restrict__ P,
                                                          int m_upper, int m_cap,
                                                          const int *__restrict__ m_dev, int N, int K,
-                                                         int kt_per_split, int frac_units) {
+                                                         int kt_per_split, int frac_units, int flags) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN, NW = WM * WN;
     constexpr int CA = BM / (8 * NW), CW = BN / (8 * NW);     // load instructions per thread per tile
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "whole load instructions per thread");
     constexpr int STAGE_CHUNKS = (BM + BN) * 8;
     static_assert((STAGES - 2) * (CA + CW) < 64, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
@@ -69,13 +75,29 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
         slot = blockIdx.x - (tile * kt_total) / frac_units;
         unit += nk;
     } else {
-        m0 = blockIdx.y * BM;
-        n0 = blockIdx.x * BN;
-        kt0 = blockIdx.z * kt_per_split;
+        int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+        if (flags & GEMM_FLAG_XCD_GROUP) {
+            // position of this workgroup in the order "XCD 0's share, XCD 1's share, ..." of the sequence
+            // (K slice, group of 4 tile rows, tile column, tile row within the group)
+            const int gx = gridDim.x, gy = gridDim.y, total = gx * gy * gridDim.z;   // host: total % 8 == 0
+            const int id = bx + gx * (by + gy * bz);
+            const int pos = (id & 7) * (total >> 3) + (id >> 3);
+            bz = pos / (gx * gy);
+            const int p2 = pos - bz * gx * gy;
+            const int grp = p2 / (4 * gx), within = p2 - grp * 4 * gx;
+            const int rows_in_grp = min(4, gy - grp * 4);
+            by = grp * 4 + within % rows_in_grp;
+            bx = within / rows_in_grp;
+        }
+        m0 = by * BM;
+        n0 = bx * BN;
+        kt0 = bz * kt_per_split;
         nk = min(kt_total, kt0 + kt_per_split) - kt0;
-        slot = blockIdx.z;
+        slot = bz;
     }
     if (m0 < M) {
+    // first K tile of this workgroup's loop (the loop wraps around the slice)
+    const int kt_rot = (flags & GEMM_FLAG_STAGGER) ? (int)((unsigned)(n0 / BN * 5 + m0 / BM * 3) % (unsigned)nk) : 0;
 
     // Source pointer of each load instruction for K tile kt0. Slot s of a stage holds row s/8, and in
     // position s%8 the chunk (s%8) ^ ((row>>1)&7). Rows past the end are clamped: they only feed outputs
@@ -94,7 +116,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
     // Tiles past the slice are clamped to its last tile: the load count per step stays constant (so one
     // vmcnt value fits every iteration) and the redundant data lands in a stage nobody reads.
     auto issue = [&](int t, int stage) {
-        const size_t koff = (size_t)min(t, nk - 1) * BK;
+        int tt = min(t, nk - 1) + kt_rot;
+        if (tt >= nk) tt -= nk;
+        const size_t koff = (size_t)tt * BK;
         const uint32_t base = lds_base + (uint32_t)(stage * STAGE_CHUNKS + wave_u * 64) * 16u;
 #pragma unroll
         for (int i = 0; i < CA; ++i) dma16(pa[i] + koff, base + (uint32_t)(i * NW * 64) * 16u);
@@ -303,11 +327,15 @@ constexpr KindInfo kKinds[] = {
     {128, 128},   // GEMM_DMA_128x128  <2,2,2,2> 3 stages
     {128, 256},   // GEMM_DMA_128x256  <2,4,2,2> 3 stages
     {256, 256},   // GEMM_DMA_256x256  <4,4,2,2> 2 stages
+    {128, 96},    // GEMM_DMA_128x96   <1,3,4,1> 4 stages
+    {128, 192},   // GEMM_DMA_128x192  <2,3,2,2> 3 stages
 };
+static_assert(sizeof(kKinds) / sizeof(kKinds[0]) == GEMM_DMA_128x192 + 1, "one entry per gemm_dma kind");
+
 
 template <int MT, int NT, int WM, int WN, int STAGES>
 int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, const int *m_dev, int n, int k,
-               int split, int frac_units, hipStream_t s) {
+               int split, int frac_units, int flags, hipStream_t s) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
     constexpr int smem = STAGES * (BM + BN) * 128;
     static bool attr_set = false;
@@ -318,9 +346,13 @@ int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, c
     }
     const int kt_total = k / BK, kps = ceil_div(kt_total, split);
     dim3 grid(ceil_div(n, BN), ceil_div(m_upper, BM), ceil_div(kt_total, kps));
-    if (frac_units) grid = dim3(ceil_div(grid.x * grid.y * kt_total, frac_units), 1, 1);
+    if (frac_units) {
+        grid = dim3(ceil_div(grid.x * grid.y * kt_total, frac_units), 1, 1);
+        flags = 0;
+    }
+    if ((grid.x * grid.y * grid.z) % 8 != 0 || grid.y < 4) flags &= ~GEMM_FLAG_XCD_GROUP;
     hipLaunchKernelGGL((gemm_dma<MT, NT, WM, WN, STAGES>), grid, dim3(64 * WM * WN), smem, s, (const bf16_t *)A,
-                       (const bf16_t *)W, P, m_upper, m_cap, m_dev, n, k, kps, frac_units);
+                       (const bf16_t *)W, P, m_upper, m_cap, m_dev, n, k, kps, frac_units, flags);
     DKV_LAUNCH_CHECK();
     return DKV_OK;
 }
@@ -337,6 +369,7 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     GemmPlan p;
     p.split_k = 1;
     p.frac_units = 0;
+    p.flags = 0;
     if (dtype != DKV_BF16 || (k % 8) != 0) {
         p.kind = GEMM_SIMT;
         return p;
@@ -345,40 +378,60 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
         p.kind = GEMM_REG_64x128;
         return p;
     }
-    // Tile shape and K split from a sweep of every (kernel, split) pair over the LLaDA-8B layer shapes at row
-    // counts 16..512 on MI355X. Wide outputs (QKV, gate/up) have enough column tiles to fill the chip alone and
-    // take the largest tile the row count uses fully; narrow outputs (O, down: N = d_model) keep tiles small
-    // and split K instead, more so when K is long.
-    const bool wide = n >= 8192, very_wide = n >= 16384, long_k = k >= 8192;
-    if (wide) {
-        if (m_upper <= 32) p.kind = GEMM_DMA_32x128;
-        else if (m_upper <= 64) p.kind = GEMM_DMA_64x128;
-        else if (m_upper <= 128) p.kind = GEMM_DMA_128x128;
-        else if (m_upper <= 256) p.kind = very_wide ? GEMM_DMA_128x256 : GEMM_DMA_128x128;
-        else if (m_upper <= 768) p.kind = very_wide ? GEMM_DMA_256x256 : GEMM_DMA_128x256;
-        else p.kind = GEMM_DMA_256x256;
-    } else {
-        if (m_upper <= 32) p.kind = GEMM_DMA_32x128;
-        else if (m_upper <= 64) p.kind = long_k ? GEMM_DMA_64x128 : GEMM_DMA_32x128;
-        else if (m_upper <= 256) p.kind = long_k ? GEMM_DMA_128x128 : GEMM_DMA_64x128;
-        else if (m_upper <= 768) p.kind = long_k ? GEMM_DMA_128x256 : GEMM_DMA_128x128;
-        else if (m_upper <= 2048) p.kind = GEMM_DMA_128x256;
-        else p.kind = GEMM_DMA_256x256;
-    }
-    const KindInfo &ki = kKinds[p.kind];
-    const int tiles = ceil_div(m_upper, ki.bm) * ceil_div(n, ki.bn);
-    int s = 256 / tiles;
+    // Tile shape and K split: the candidate with the smallest predicted launch time. The prediction is a
+    // small model of this kernel on MI355X, its constants fitted to a sweep of every (tile shape, split)
+    // over the layer shapes of the 8B and 7B models at 16..12288 rows (mean loss against the best measured
+    // candidate 2 %, worst 24 %):
+    //   a workgroup needs, per K tile, the longer of filling its LDS stage (~49 GB/s per compute unit, and
+    //   ~14 TB/s over all workgroups in flight) and its MFMAs (~5.3 TFLOP/s per compute unit);
+    //   workgroups run in rounds of 256 (one per compute unit), a partly filled round costs a full one;
+    //   no launch beats streaming its operands and results once;
+    //   K slices add the write and re-read of their partial sums by the consumer.
+    // Tiles of 96 and 192 columns exist because 12288 / 96 = 128 and 24576 / 192 = 128 column tiles make
+    // exactly one or two full rounds where 128- and 256-column tiles leave a quarter of the chip idle.
+    constexpr double kFillPerCu = 48785.0, kFlopsPerCu = 5332277.0, kFillAll = 14076233.0;   // bytes, flops per us
+    constexpr double kStream = 7841520.0, kReduce = 1819886.0;                                  // bytes per us
+    constexpr double kLaunch = 3.5, kPipeFill = 0.7, kReduceFixed = 1.7;                        // us
+    static const int kSplits[] = {1, 2, 3, 4, 6, 8};
     const int kt_total = k / BK;
-    const int max_s = kt_total / 8 > 0 ? kt_total / 8 : 1;      // at least 8 K tiles per slice
-    if (s > 8) s = 8;
-    if (s > max_s) s = max_s;
-    if (s == 5) s = 4;                                          // uneven slices cost more than they fill
-    if (s == 7) s = 6;
-    if (s < 1) s = 1;
-    p.split_k = effective_split(k, s);
-    // Shapes with 192 tiles leave a quarter of the 256 compute units idle. Giving 256 workgroups 3/4 of a
-    // tile's K range each (frac_units, kept for experiments through dkv_gemm_with) fills the chip but was
-    // measured to take the same time: those launches are bound by total L2-to-LDS traffic, not per unit.
+    double best = 0.0;
+    p.kind = -1;
+    for (int kind = 0; kind <= GEMM_DMA_128x192; ++kind) {
+        const KindInfo &ki = kKinds[kind];
+        if (ki.bm > 32 && ki.bm >= 4 * m_upper) continue;       // mostly padding
+        if (ki.bm < 128 && m_upper > 4 * ki.bm) continue;       // W re-read too often
+        const int tiles = ceil_div(m_upper, ki.bm) * ceil_div(n, ki.bn);
+        const double fill = (ki.bm + ki.bn) * 128.0, flops = 2.0 * ki.bm * ki.bn * BK;
+        for (int s : kSplits) {
+            const int nk = ceil_div(kt_total, s);
+            if (ceil_div(kt_total, nk) != s || (s > 1 && nk < 8)) continue;
+            const long wgs = (long)tiles * s;
+            const long rounds = (wgs + 255) / 256;
+            double t_tile = fill / kFillPerCu;
+            if (flops / kFlopsPerCu > t_tile) t_tile = flops / kFlopsPerCu;
+            const double in_flight = (double)(wgs < 256 ? wgs : 256);
+            if (in_flight * fill / kFillAll > t_tile) t_tile = in_flight * fill / kFillAll;
+            double t = rounds * (nk * t_tile + kPipeFill);
+            const double stream = (2.0 * n * k + 2.0 * m_upper * (double)k + 4.0 * s * m_upper * (double)n) / kStream;
+            if (stream > t) t = stream;
+            t += kLaunch;
+            if (s > 1) t += (s + 1) * 4.0 * m_upper * (double)n / kReduce + kReduceFixed;
+            if (p.kind < 0 || t < best) {
+                best = t;
+                p.kind = kind;
+                p.split_k = s;
+            }
+        }
+    }
+    // Launch options, from the same sweep: a staggered K start pays when one row of tiles sweeps K unsplit or
+    // in two slices (all workgroups would otherwise read the same A columns at once); the XCD-grouped order
+    // pays for the two largest tiles once there are enough tile rows to form 4-row groups.
+    const int tiles_m = ceil_div(m_upper, kKinds[p.kind].bm);
+    if (tiles_m == 1 && p.split_k <= 2) p.flags |= GEMM_FLAG_STAGGER;
+    if ((p.kind == GEMM_DMA_256x256 && tiles_m >= 4) || (p.kind == GEMM_DMA_128x256 && tiles_m >= 6))
+        p.flags |= GEMM_FLAG_XCD_GROUP;
+    // Giving 256 workgroups 3/4 of a tile's K range each (frac_units, kept for experiments through
+    // dkv_gemm_with) was measured to take the same time as two full slices, so it is never planned.
     return p;
 }
 
@@ -386,7 +439,7 @@ int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p) {
     if (p.split_k < 1 || p.kind < 0 || p.kind >= GEMM_KINDS || p.frac_units < 0) return 0;
     if (p.frac_units) {
         // a 3/4 share: every tile is covered by exactly two workgroups
-        if (p.kind > GEMM_DMA_256x256 || dtype != DKV_BF16 || (k % BK) != 0) return 0;
+        if (p.kind > GEMM_DMA_128x192 || dtype != DKV_BF16 || (k % BK) != 0) return 0;
         return p.split_k == 2 && (k / BK) % 4 == 0 && p.frac_units == (k / BK) * 3 / 4;
     }
     if (p.kind == GEMM_SIMT) return p.split_k == 1;
@@ -404,15 +457,19 @@ int dkv_launch_gemm(int dtype, const void *A, const void *W, float *partial, int
     }
     switch (p.kind) {
         case GEMM_DMA_32x128:
-            return launch_dma<1, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
+            return launch_dma<1, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
         case GEMM_DMA_64x128:
-            return launch_dma<2, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
+            return launch_dma<2, 1, 1, 4, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
         case GEMM_DMA_128x128:
-            return launch_dma<2, 2, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
+            return launch_dma<2, 2, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
         case GEMM_DMA_128x256:
-            return launch_dma<2, 4, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
+            return launch_dma<2, 4, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
         case GEMM_DMA_256x256:
-            return launch_dma<4, 4, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, stream);
+            return launch_dma<4, 4, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
+        case GEMM_DMA_128x96:
+            return launch_dma<1, 3, 4, 1, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
+        case GEMM_DMA_128x192:
+            return launch_dma<2, 3, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
         case GEMM_REG_64x128: {
             const int kt_total = ceil_div(k, BK), kps = ceil_div(kt_total, p.split_k);
             dim3 grid(ceil_div(n, 128), ceil_div(m_upper, 64), p.split_k);

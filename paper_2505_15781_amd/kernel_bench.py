@@ -19,7 +19,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4])
     ap.add_argument("--rows", default="2,32,64,128,192,256,512")
-    ap.add_argument("--reps", type=int, default=4)
+    ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--copy-calibration", action="store_true")
     args = ap.parse_args()
     import torch
@@ -51,8 +51,9 @@ def main():
             def run(w):
                 _check(lib.dkv_gemm(_ptr(x), _ptr(w), _ptr(y), M, N, K, binding.BF16, _ptr(ws), nb, _stream()))
 
-            for w in Ws:
-                run(w)
+            for _ in range(3):                 # warm-up: clocks and caches in the state of a running model
+                for w in Ws:
+                    run(w)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()

@@ -31,7 +31,8 @@ def test_projection_matches_float64_product(dtype, m, n, k):
 
 @pytest.mark.parametrize("kind,split", [("dma_32x128", 1), ("dma_32x128", 3), ("dma_64x128", 2), ("dma_128x128", 1),
                                         ("dma_128x128", 4), ("dma_128x256", 2), ("dma_256x256", 1),
-                                        ("dma_256x256", 3), ("reg_64x128", 2)])
+                                        ("dma_256x256", 3), ("dma_128x96", 1), ("dma_128x96", 2),
+                                        ("dma_128x192", 1), ("dma_128x192", 3), ("reg_64x128", 2)])
 @pytest.mark.parametrize("m,n,k", [(1, 128, 64), (37, 200, 192), (129, 384, 1024), (300, 520, 640), (513, 256, 2048)])
 def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
     import paper_2505_15781_amd as P
@@ -46,6 +47,30 @@ def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
     y = P.gemm(_dev(x, BF16), _dev(w, BF16), BF16, kind=kind, split_k=split_eff).cpu().numpy()
     ref = x.astype(np.float64) @ w.astype(np.float64).T
     check_close(y, ref, 1e-5, f"{kind} split {split_eff} {m}x{n}x{k}")
+
+
+@pytest.mark.parametrize("kind", ["dma_32x128", "dma_64x128", "dma_128x128", "dma_128x256", "dma_256x256",
+                                  "dma_128x96", "dma_128x192"])
+@pytest.mark.parametrize("options", [1, 2, 3])
+@pytest.mark.parametrize("m,n,k,split", [(5, 128, 256, 1), (129, 384, 1024, 1), (300, 520, 768, 2),
+                                         (1100, 1536, 512, 1), (1030, 2048, 640, 2)])
+def test_projection_launch_options_leave_the_product_unchanged(kind, options, m, n, k, split):
+    """A staggered K loop start and the XCD-grouped tile order only permute work: same product (up to fp32
+    summation order); the last two shapes have at least four tile rows, so the grouping is really applied."""
+    import paper_2505_15781_amd as P
+    x = D.normal_f32(9, 1, (m, k), bf16=True)
+    w = D.normal_f32(9, 2, (n, k), std=0.02, bf16=True)
+    y = P.gemm(_dev(x, BF16), _dev(w, BF16), BF16, kind=kind, split_k=split, options=options).cpu().numpy()
+    check_close(y, x.astype(np.float64) @ w.astype(np.float64).T, 1e-5, f"{kind} options {options} {m}x{n}x{k}")
+
+
+def test_projection_rejects_unknown_option_bits():
+    import paper_2505_15781_amd as P
+    x = _dev(D.normal_f32(6, 1, (4, 64), bf16=True), BF16)
+    w = _dev(D.normal_f32(6, 2, (8, 64), bf16=True), BF16)
+    with pytest.raises(P.DkvError) as e:
+        P.gemm(x, w, BF16, kind="dma_32x128", split_k=1, options=8)
+    assert e.value.code == -1
 
 
 @pytest.mark.parametrize("kind", ["dma_32x128", "dma_64x128", "dma_128x128", "dma_128x256", "dma_256x256"])
