@@ -1,14 +1,15 @@
 // Bidirectional attention of the active queries over the full-length, position-indexed K/V cache
 // (Eq. 4: softmax(Q^{A_t} K^{I T} / sqrt(d)) V^I, no mask; query heads of one group share a K/V head).
 //
-// bf16 kernel: one wavefront owns one work item = (sequence, kv head, 16 query rows, key slice), where
-// a "query row" is an (active row, query head of the group) pair. It streams its key slice in tiles
-// of 32 keys: K rows and a transposed copy of the V rows go through a wave-private LDS region, the
-// next tile's global loads are in flight while the current tile is multiplied. Scores are formed
+// bf16 kernels (attn_ksplit.h, attn_shared.h): a "query row" is an (active row, query head of the group)
+// pair, handled in tiles of 16. Keys stream in tiles through LDS (K rows and a transposed copy of the V
+// rows), the next tile's global loads are in flight while the current tile is multiplied. Scores are formed
 // transposed (keys x queries) so the probabilities come out of the MFMA already laid out as the
 // operand of the second product and never leave registers; the output accumulates transposed
-// (head_dim x queries) with a running max / sum per query (online softmax). With several key
-// slices every item writes (max, sum, unnormalised output) and a second kernel merges them.
+// (head_dim x queries) with a running max / sum per query (online softmax). The key-split kernel deals
+// the key tiles to the wavefronts of a workgroup and merges their states in LDS; the shared kernel
+// gives every wavefront its own query tiles over one shared K/V tile. When the keys are also sliced
+// across workgroups every workgroup writes (max, sum, unnormalised output) and attn_merge combines them.
 //
 // generic kernel (fp32 mode and odd head sizes): one wavefront per (row, query head), lanes stride
 // over the keys, fp32 FMA, exact expf.
@@ -66,170 +67,8 @@ __device__ __forceinline__ void softmax_step(f32x4 (&st)[NT], float &m_run, floa
     for (int mt = 0; mt < NACC; ++mt) acc[mt] *= alpha;
 }
 
-template <int DH>
-__global__ __launch_bounds__(256) void attn_bf16_mfma(
-    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
-    const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
-    int Hq, int Hkv, int L, int q_tiles, int splits, int tiles_per_split, int rows_cap,
-    float scale_log2e) {
-    using SM = AttnSmem<DH>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    unsigned char *ksm = smem_raw + wave * SM::WAVE_BYTES;
-    unsigned char *vsm = ksm + SM::K_BYTES;
-
-    const int G = Hq / Hkv;
-    long item = (long)blockIdx.x * 4 + wave;
-    const long n_items = (long)batch * Hkv * q_tiles * splits;
-    if (item >= n_items) return;
-    const int split = (int)(item % splits); item /= splits;
-    const int qt = (int)(item % q_tiles);   item /= q_tiles;
-    const int kvh = (int)(item % Hkv);
-    const int b = (int)(item / Hkv);
-
-    const int r0 = row_off[b], nrows = row_off[b + 1] - r0;
-    const int nq = nrows * G;                    // query rows of this (sequence, kv head)
-    const int m0 = qt * 16;
-    if (m0 >= nq) return;
-
-    const int qi = lane & 15, g = lane >> 4;
-    // my query column: (row, head)
-    const int mq = m0 + qi;
-    // rows beyond the host's bound have no slot in the output or partial buffers
-    const bool q_ok = mq < nq && r0 + mq / G < rows_cap;
-    const int q_row = q_ok ? r0 + mq / G : 0, q_head = kvh * G + (q_ok ? mq % G : 0);
-
-    bf16x8 qf[DH / 32];
-    {
-        const bf16_t *qp = Q + ((size_t)q_row * Hq + q_head) * DH + 8 * g;
-#pragma unroll
-        for (int ks = 0; ks < DH / 32; ++ks) {
-            uint4 v = q_ok ? *reinterpret_cast<const uint4 *>(qp + 32 * ks) : make_uint4(0, 0, 0, 0);
-            qf[ks] = *reinterpret_cast<bf16x8 *>(&v);
-        }
-    }
-
-    const bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
-    const bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
-    const int n_tiles = (L + KT - 1) / KT;
-    const int t0 = split * tiles_per_split, t1 = min(n_tiles, t0 + tiles_per_split);
-
-    // global -> register staging of one tile
-    constexpr int KCH = KT * DH / 8 / 64;        // 16-byte K chunks per lane
-    constexpr int VTASK = (KT / 4) * (DH / 8) / 64;   // (4 keys x 8 dims) transposition tasks per lane
-    uint4 kreg[KCH], vreg[VTASK][4];
-    auto load_tile = [&](int t) {
-        const int key0 = t * KT;
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            int c = lane + 64 * i, key = c / (DH / 8), ch = c % (DH / 8);
-            int gk = key0 + key;
-            kreg[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8)
-                             : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < VTASK; ++i) {
-            int task = lane + 64 * i, dc = task % (DH / 8), kg = task / (DH / 8);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                int gk = key0 + 4 * kg + j;
-                vreg[i][j] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + dc * 8)
-                                    : make_uint4(0, 0, 0, 0);
-            }
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            int c = lane + 64 * i, key = c / (DH / 8), ch = c % (DH / 8);
-            *reinterpret_cast<uint4 *>(ksm + key * SM::K_STRIDE + ch * 16) = kreg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < VTASK; ++i) {
-            int task = lane + 64 * i, dc = task % (DH / 8), kg = task / (DH / 8);
-            const uint32_t *v0 = reinterpret_cast<const uint32_t *>(&vreg[i][0]);
-            const uint32_t *v1 = reinterpret_cast<const uint32_t *>(&vreg[i][1]);
-            const uint32_t *v2 = reinterpret_cast<const uint32_t *>(&vreg[i][2]);
-            const uint32_t *v3 = reinterpret_cast<const uint32_t *>(&vreg[i][3]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {     // word e holds dims 2e (low half) and 2e+1 (high half)
-                uint2 lo = make_uint2(pack_lo(v0[e], v1[e]), pack_lo(v2[e], v3[e]));
-                uint2 hi = make_uint2(pack_hi(v0[e], v1[e]), pack_hi(v2[e], v3[e]));
-                int d = dc * 8 + 2 * e;
-                *reinterpret_cast<uint2 *>(vsm + d * SM::VT_STRIDE + kg * 8) = lo;
-                *reinterpret_cast<uint2 *>(vsm + (d + 1) * SM::VT_STRIDE + kg * 8) = hi;
-            }
-        }
-    };
-
-    float m_run = -INFINITY, l_run = 0.f;
-    f32x4 acc[DH / 16];
-#pragma unroll
-    for (int i = 0; i < DH / 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    if (t0 < t1) load_tile(t0);
-    for (int t = t0; t < t1; ++t) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        store_tile();
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        if (t + 1 < t1) load_tile(t + 1);
-
-        // S^T[key][query] for the two 16-key halves of the tile
-        f32x4 st[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            st[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const unsigned char *krow = ksm + (16 * j + qi) * SM::K_STRIDE + g * 16;
-#pragma unroll
-            for (int ks = 0; ks < DH / 32; ++ks) {
-                bf16x8 kf = *reinterpret_cast<const bf16x8 *>(krow + ks * 64);
-                st[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], st[j], 0, 0, 0);
-            }
-        }
-        // st[j][i] belongs to key 16j + 4g + i and query qi
-        bf16x8 pbv[1];
-        softmax_step<2, DH / 16>(st, m_run, l_run, acc, pbv, t * KT + 4 * g, L, (t + 1) * KT > L, scale_log2e);
-        const bf16x8 pb = pbv[0];
-#pragma unroll
-        for (int mt = 0; mt < DH / 16; ++mt) {
-            const unsigned char *vrow = vsm + (16 * mt + qi) * SM::VT_STRIDE;
-            uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + g * 8);          // keys 4g..4g+3
-            uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 + g * 8);     // keys 16+4g..
-            uint4 av = make_uint4(a0.x, a0.y, a1.x, a1.y);
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&av), pb, acc[mt],
-                                                               0, 0, 0);
-        }
-    }
-
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
-    if (!q_ok) return;
-    if (splits == 1) {
-        const float inv = 1.f / l_run;
-        bf16_t *op = out + ((size_t)q_row * Hq + q_head) * DH;
-#pragma unroll
-        for (int mt = 0; mt < DH / 16; ++mt) {
-            uint2 w;
-            w.x = (uint32_t)f2bf(acc[mt][0] * inv) | ((uint32_t)f2bf(acc[mt][1] * inv) << 16);
-            w.y = (uint32_t)f2bf(acc[mt][2] * inv) | ((uint32_t)f2bf(acc[mt][3] * inv) << 16);
-            *reinterpret_cast<uint2 *>(op + 16 * mt + 4 * g) = w;
-        }
-    } else {
-        // partial record per (query row-head, split): [m, l, pad, pad, o[DH]]
-        float *rec = part + (((size_t)q_row * Hq + q_head) * splits + split) * (DH + 4);
-        if (g == 0) {
-            rec[0] = m_run;
-            rec[1] = l_run;
-        }
-#pragma unroll
-        for (int mt = 0; mt < DH / 16; ++mt)
-            *reinterpret_cast<f32x4 *>(rec + 4 + 16 * mt + 4 * g) = acc[mt];
-    }
-}
-
 #include "attn_shared.h"
+#include "attn_ksplit.h"
 
 // Merge the key slices of one (row, head): one wavefront per pair.
 template <int DH>
@@ -342,23 +181,41 @@ AttnPlan dkv_attn_plan(int dtype, int batch, int n_q_heads, int n_kv_heads, int 
     p.use_mfma = (dtype == DKV_BF16 && (head_dim == 64 || head_dim == 128)) ? 1 : 0;
     p.shared_nq = 0;
     p.q_blocks = 0;
+    p.ksplit_nq = 0;
+    p.ksplit_waves = 0;
+    p.q_groups = 0;
     int G = n_q_heads / n_kv_heads;
     p.q_tiles = ceil_div(max_rows_per_seq * G, 16);
     if (p.q_tiles < 1) p.q_tiles = 1;
-    int s = 1, n_tiles;
-    if (p.use_mfma && head_dim == 128 && p.q_tiles >= 4) {
-        // enough query rows to give every wavefront of a workgroup its own tile(s)
-        p.shared_nq = p.q_tiles >= 8 ? 2 : 1;
-        p.q_blocks = ceil_div(p.q_tiles, 4 * p.shared_nq);
-        n_tiles = ceil_div(seq_len, 64);
-        long items = (long)batch * n_kv_heads * p.q_blocks;
-        if (items < 512) s = (int)((512 + items - 1) / items);
-    } else {
-        n_tiles = ceil_div(seq_len, KT);
-        long items = (long)batch * n_kv_heads * p.q_tiles;
-        if (p.use_mfma && items < 2048) s = (int)((2048 + items - 1) / items);
+    if (!p.use_mfma) {
+        p.splits = 1;
+        p.tiles_per_split = ceil_div(seq_len, KT);
+        return p;
     }
-    int max_s = n_tiles / 2 > 0 ? n_tiles / 2 : 1;      // at least two tiles per slice
+    // Measured on MI355X over the shapes of the four workloads: the key-split kernel wins unless there are
+    // many query tiles per kv head that fill the shared kernel's blocks of 8 tiles well and enough blocks to
+    // occupy the chip without slicing the keys (then the shared K/V tiles save L2 traffic and staging work).
+    const int blocks8 = ceil_div(p.q_tiles, 8);
+    const bool shared = head_dim == 128 && p.q_tiles >= 16 && (long)batch * n_kv_heads * blocks8 >= 256 &&
+                        (blocks8 * 8 - p.q_tiles) * 10 <= p.q_tiles;
+    int s = 1, n_tiles, min_tiles;
+    if (shared) {
+        p.shared_nq = 2;
+        p.q_blocks = blocks8;
+        n_tiles = ceil_div(seq_len, 64);
+        min_tiles = 2;
+    } else {
+        p.ksplit_nq = p.q_tiles >= 2 ? 2 : 1;
+        p.q_groups = ceil_div(p.q_tiles, p.ksplit_nq);
+        n_tiles = ceil_div(seq_len, KT);
+        const long items = (long)batch * n_kv_heads * p.q_groups;
+        // 8 wavefronts per workgroup (one workgroup per compute unit) while that still gives every compute
+        // unit at most one; beyond, 4 wavefronts so that two workgroups share a unit
+        p.ksplit_waves = items <= 256 ? 8 : 4;
+        if (items < 192) s = (int)((384 + items - 1) / items);
+        min_tiles = 2 * p.ksplit_waves;                     // two tiles per wavefront
+    }
+    const int max_s = n_tiles / min_tiles > 0 ? n_tiles / min_tiles : 1;
     if (s > max_s) s = max_s;
     p.tiles_per_split = ceil_div(n_tiles, s);
     p.splits = ceil_div(n_tiles, p.tiles_per_split);
@@ -385,11 +242,55 @@ int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const vo
         return launch_generic<float>(q, k_cache, v_cache, row_off, out, batch, n_q_heads, n_kv_heads,
                                      seq_len, head_dim, rows_upper, stream);
     }
-    long items = (long)batch * n_kv_heads * plan.q_tiles * plan.splits;
-    dim3 grid((unsigned)((items + 3) / 4));
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
     long pairs = (long)rows_upper * n_q_heads;
-    if (plan.shared_nq) {
+    if (plan.ksplit_nq) {
+        const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_groups * plan.splits);
+#define KSPLIT(D, NQ, NW)                                                                                      \
+    do {                                                                                                       \
+        static bool lds_ok = false;                                                                            \
+        const size_t smem = NW * AttnSmem<D>::WAVE_BYTES;                                                      \
+        if (!lds_ok) {                                                                                         \
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_ksplit<D, NQ, NW>),      \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));           \
+            lds_ok = true;                                                                                     \
+        }                                                                                                      \
+        hipLaunchKernelGGL((attn_bf16_ksplit<D, NQ, NW>), dim3(wgs), dim3(64 * NW), smem, stream,              \
+                           (const bf16_t *)q, (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off,       \
+                           (bf16_t *)out, (float *)partial, batch, n_q_heads, n_kv_heads, seq_len,             \
+                           plan.q_groups, plan.splits, plan.tiles_per_split, rows_upper, scale_log2e);         \
+    } while (0)
+        if (head_dim == 128) {
+            if (plan.ksplit_waves == 8) {
+                if (plan.ksplit_nq == 2) KSPLIT(128, 2, 8);
+                else KSPLIT(128, 1, 8);
+            } else {
+                if (plan.ksplit_nq == 2) KSPLIT(128, 2, 4);
+                else KSPLIT(128, 1, 4);
+            }
+        } else {
+            if (plan.ksplit_waves == 8) {
+                if (plan.ksplit_nq == 2) KSPLIT(64, 2, 8);
+                else KSPLIT(64, 1, 8);
+            } else {
+                if (plan.ksplit_nq == 2) KSPLIT(64, 2, 4);
+                else KSPLIT(64, 1, 4);
+            }
+        }
+#undef KSPLIT
+        DKV_LAUNCH_CHECK();
+        if (plan.splits > 1) {
+            if (head_dim == 128)
+                hipLaunchKernelGGL((attn_merge<128>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream,
+                                   (const float *)partial, (bf16_t *)out, row_off, batch, n_q_heads, plan.splits,
+                                   rows_upper);
+            else
+                hipLaunchKernelGGL((attn_merge<64>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream,
+                                   (const float *)partial, (bf16_t *)out, row_off, batch, n_q_heads, plan.splits,
+                                   rows_upper);
+            DKV_LAUNCH_CHECK();
+        }
+    } else if (plan.shared_nq) {
         const size_t smem = 2 * (64 * (128 * 2 + 16) + 128 * (64 * 2 + 8));
         const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_blocks * plan.splits);
         static bool lds_ok1 = false, lds_ok2 = false;
@@ -419,44 +320,6 @@ int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const vo
             hipLaunchKernelGGL((attn_merge<128>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream,
                                (const float *)partial, (bf16_t *)out, row_off, batch, n_q_heads, plan.splits,
                                rows_upper);
-            DKV_LAUNCH_CHECK();
-        }
-    } else if (head_dim == 128) {
-        size_t smem = 4 * AttnSmem<128>::WAVE_BYTES;
-        static bool lds_ok = false;
-        if (!lds_ok) {
-            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_mfma<128>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-            lds_ok = true;
-        }
-        hipLaunchKernelGGL((attn_bf16_mfma<128>), grid, dim3(256), smem, stream, (const bf16_t *)q,
-                           (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out,
-                           (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_tiles,
-                           plan.splits, plan.tiles_per_split, rows_upper, scale_log2e);
-        DKV_LAUNCH_CHECK();
-        if (plan.splits > 1) {
-            hipLaunchKernelGGL((attn_merge<128>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream,
-                               (const float *)partial, (bf16_t *)out, row_off, batch, n_q_heads,
-                               plan.splits, rows_upper);
-            DKV_LAUNCH_CHECK();
-        }
-    } else {
-        size_t smem = 4 * AttnSmem<64>::WAVE_BYTES;
-        static bool lds_ok = false;
-        if (!lds_ok) {
-            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_mfma<64>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-            lds_ok = true;
-        }
-        hipLaunchKernelGGL((attn_bf16_mfma<64>), grid, dim3(256), smem, stream, (const bf16_t *)q,
-                           (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out,
-                           (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_tiles,
-                           plan.splits, plan.tiles_per_split, rows_upper, scale_log2e);
-        DKV_LAUNCH_CHECK();
-        if (plan.splits > 1) {
-            hipLaunchKernelGGL((attn_merge<64>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream,
-                               (const float *)partial, (bf16_t *)out, row_off, batch, n_q_heads,
-                               plan.splits, rows_upper);
             DKV_LAUNCH_CHECK();
         }
     }

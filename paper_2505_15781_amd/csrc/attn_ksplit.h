@@ -1,0 +1,216 @@
+// Attention kernel for small and medium active sets: the NW (4 or 8) wavefronts of a workgroup split the keys.
+// Included by attention.hip (uses its helpers).
+//
+// Work item = (sequence, kv head, group of NQ query tiles of 16 rows, key slice). The workgroup's key
+// tiles (32 keys each) are dealt round-robin to its wavefronts; every wavefront streams its tiles through a
+// private LDS region exactly as attn_bf16_mfma does (K rows and transposed V, next tile's global loads in
+// flight during the products) and keeps an online softmax for its NQ query tiles. At the end the NW
+// (max, sum, unnormalised output) states meet in LDS and are merged there, so with one key slice per item the
+// normalised bf16 output is written directly: no partial records in global memory and no merge launch. With
+// several key slices the merged state of the workgroup is one partial record (a quarter of what one record
+// per wavefront would need) for attn_merge.
+#pragma once
+
+template <int DH, int NQ, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
+    const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
+    int Hq, int Hkv, int L, int q_groups, int splits, int tiles_per_split, int rows_cap,
+    float scale_log2e) {
+    using SM = AttnSmem<DH>;
+    constexpr int REC = DH + 4;                       // floats per merged row: m, l, pad, pad, o[DH]
+    static_assert(NQ * 16 * REC * 4 <= SM::WAVE_BYTES, "merge records fit the wavefront's LDS region");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    unsigned char *ksm = smem_raw + wave * SM::WAVE_BYTES;
+    unsigned char *vsm = ksm + SM::K_BYTES;
+
+    const int G = Hq / Hkv;
+    long item = blockIdx.x;
+    const int split = (int)(item % splits);   item /= splits;
+    const int qg = (int)(item % q_groups);    item /= q_groups;
+    const int kvh = (int)(item % Hkv);
+    const int b = (int)(item / Hkv);
+    if (b >= batch) return;
+
+    const int r0 = row_off[b], nrows = row_off[b + 1] - r0;
+    const int nq = nrows * G;                    // query rows of this (sequence, kv head)
+    const int m0 = qg * NQ * 16;
+    if (m0 >= nq) return;                        // uniform for the workgroup: no barrier is skipped by part of it
+
+    const int qi = lane & 15, g = lane >> 4;
+    bf16x8 qf[NQ][DH / 32];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const int mq = m0 + 16 * j + qi;
+        // rows beyond the host's bound have no slot in the output or partial buffers
+        const bool ok = mq < nq && r0 + mq / G < rows_cap;
+        const bf16_t *qp = Q + ((size_t)(ok ? r0 + mq / G : 0) * Hq + kvh * G + (ok ? mq % G : 0)) * DH + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < DH / 32; ++ks) {
+            uint4 v = ok ? *reinterpret_cast<const uint4 *>(qp + 32 * ks) : make_uint4(0, 0, 0, 0);
+            qf[j][ks] = *reinterpret_cast<bf16x8 *>(&v);
+        }
+    }
+
+    const bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    const bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    const int n_tiles = (L + KT - 1) / KT;
+    const int t_begin = split * tiles_per_split, t_end = min(n_tiles, t_begin + tiles_per_split);
+
+    constexpr int KCH = KT * DH / 8 / 64;             // 16-byte K chunks per lane
+    constexpr int VTASK = (KT / 4) * (DH / 8) / 64;   // (4 keys x 8 dims) transposition tasks per lane
+    uint4 kreg[KCH], vreg[VTASK][4];
+    auto load_tile = [&](int t) {
+        const int key0 = t * KT;
+#pragma unroll
+        for (int i = 0; i < KCH; ++i) {
+            const int c = lane + 64 * i, key = c / (DH / 8), ch = c % (DH / 8), gk = key0 + key;
+            kreg[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < VTASK; ++i) {
+            const int task = lane + 64 * i, dc = task % (DH / 8), kg = task / (DH / 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int gk = key0 + 4 * kg + j;
+                vreg[i][j] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + dc * 8)
+                                    : make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int i = 0; i < KCH; ++i) {
+            const int c = lane + 64 * i, key = c / (DH / 8), ch = c % (DH / 8);
+            *reinterpret_cast<uint4 *>(ksm + key * SM::K_STRIDE + ch * 16) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < VTASK; ++i) {
+            const int task = lane + 64 * i, dc = task % (DH / 8), kg = task / (DH / 8);
+            const uint32_t *v0 = reinterpret_cast<const uint32_t *>(&vreg[i][0]);
+            const uint32_t *v1 = reinterpret_cast<const uint32_t *>(&vreg[i][1]);
+            const uint32_t *v2 = reinterpret_cast<const uint32_t *>(&vreg[i][2]);
+            const uint32_t *v3 = reinterpret_cast<const uint32_t *>(&vreg[i][3]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {     // word e holds dims 2e (low half) and 2e+1 (high half)
+                const uint2 lo = make_uint2(pack_lo(v0[e], v1[e]), pack_lo(v2[e], v3[e]));
+                const uint2 hi = make_uint2(pack_hi(v0[e], v1[e]), pack_hi(v2[e], v3[e]));
+                const int d = dc * 8 + 2 * e;
+                *reinterpret_cast<uint2 *>(vsm + d * SM::VT_STRIDE + kg * 8) = lo;
+                *reinterpret_cast<uint2 *>(vsm + (d + 1) * SM::VT_STRIDE + kg * 8) = hi;
+            }
+        }
+    };
+
+    float m_run[NQ], l_run[NQ];
+    f32x4 acc[NQ][DH / 16];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        m_run[j] = -INFINITY;
+        l_run[j] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DH / 16; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // this wavefront's tiles: t_begin + wave, + NW, + 2 NW, ...
+    int t = t_begin + wave;
+    if (t < t_end) load_tile(t);
+    for (; t < t_end; t += NW) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        store_tile();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (t + NW < t_end) load_tile(t + NW);
+
+        f32x4 st[NQ][2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const unsigned char *krow = ksm + (16 * h + qi) * SM::K_STRIDE + g * 16;
+#pragma unroll
+            for (int j = 0; j < NQ; ++j) st[j][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < DH / 32; ++ks) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(krow + ks * 64);
+#pragma unroll
+                for (int j = 0; j < NQ; ++j)
+                    st[j][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[j][ks], st[j][h], 0, 0, 0);
+            }
+        }
+        // st[j][h][i] is the score of key 16h + 4g + i of this tile against query qi of tile j
+        bf16x8 pb[NQ][1];
+#pragma unroll
+        for (int j = 0; j < NQ; ++j)
+            softmax_step<2, DH / 16>(st[j], m_run[j], l_run[j], acc[j], pb[j], t * KT + 4 * g, L, (t + 1) * KT > L,
+                                     scale_log2e);
+#pragma unroll
+        for (int mt = 0; mt < DH / 16; ++mt) {
+            const unsigned char *vrow = vsm + (16 * mt + qi) * SM::VT_STRIDE;
+            const uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + g * 8);          // keys 4g..4g+3
+            const uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 + g * 8);     // keys 16+4g..
+            uint4 av = make_uint4(a0.x, a0.y, a1.x, a1.y);
+#pragma unroll
+            for (int j = 0; j < NQ; ++j)
+                acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&av), pb[j][0],
+                                                                     acc[j][mt], 0, 0, 0);
+        }
+    }
+
+    // Each wavefront leaves its state in its own LDS region: record (tile j, query qi) = m, l, -, -, o[DH].
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    float *my_rec = reinterpret_cast<float *>(ksm);
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        float l = l_run[j];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        float *rec = my_rec + (j * 16 + qi) * REC;
+        if (g == 0) {
+            rec[0] = m_run[j];
+            rec[1] = l;
+        }
+#pragma unroll
+        for (int mt = 0; mt < DH / 16; ++mt) *reinterpret_cast<f32x4 *>(rec + 4 + 16 * mt + 4 * g) = acc[j][mt];
+    }
+    __syncthreads();
+
+    // Merge: thread handles (query row, 4 consecutive output dims) pairs.
+    constexpr int CHUNKS = DH / 4;
+    for (int idx = tid; idx < NQ * 16 * CHUNKS; idx += 64 * NW) {
+        const int qr = idx / CHUNKS, ch = idx % CHUNKS;     // qr = 16 j + qi
+        const int mq = m0 + qr;
+        if (mq >= nq || r0 + mq / G >= rows_cap) continue;
+        float mw[NW], M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            mw[w] = reinterpret_cast<const float *>(smem_raw + w * SM::WAVE_BYTES)[qr * REC];
+            M = fmaxf(M, mw[w]);
+        }
+        float lsum = 0.f;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float *rec = reinterpret_cast<const float *>(smem_raw + w * SM::WAVE_BYTES) + qr * REC;
+            const float wgt = mw[w] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw[w] - M);
+            lsum += wgt * rec[1];
+            o += wgt * *reinterpret_cast<const f32x4 *>(rec + 4 + 4 * ch);
+        }
+        const size_t pair = (size_t)(r0 + mq / G) * Hq + kvh * G + mq % G;
+        if (splits == 1) {
+            const float inv = 1.f / lsum;
+            uint2 wv;
+            wv.x = (uint32_t)f2bf(o[0] * inv) | ((uint32_t)f2bf(o[1] * inv) << 16);
+            wv.y = (uint32_t)f2bf(o[2] * inv) | ((uint32_t)f2bf(o[3] * inv) << 16);
+            *reinterpret_cast<uint2 *>(out + pair * DH + 4 * ch) = wv;
+        } else {
+            float *rec = part + (pair * splits + split) * REC;
+            if (ch == 0) {
+                rec[0] = M;
+                rec[1] = lsum;
+            }
+            *reinterpret_cast<f32x4 *>(rec + 4 + 4 * ch) = o;
+        }
+    }
+}

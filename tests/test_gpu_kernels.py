@@ -128,6 +128,24 @@ def test_attention_small_ragged_gqa_bf16(dh):
     _attn_case(shape, None, 33, ragged=[203, 64, 17])
 
 
+@pytest.mark.parametrize("dh", [128, 64])
+def test_attention_key_slices_across_workgroups(dh):
+    """Few (sequence, head) pairs and many keys: the keys are sliced over several workgroups and merged by
+    the second kernel; 2085 keys leave a ragged last tile and an uneven deal of tiles to the wavefronts."""
+    shape = D.AttnUpdateShape(batch=1, n_q_heads=4, n_kv_heads=2, seq_len=2085, head_dim=dh, dtype=BF16)
+    _attn_case(shape, None, 34, ragged=[21])
+    shape = D.AttnUpdateShape(batch=2, n_q_heads=2, n_kv_heads=2, seq_len=1031, head_dim=dh, dtype=BF16)
+    _attn_case(shape, None, 35, ragged=[3, 40])
+
+
+def test_attention_many_query_tiles_per_head():
+    """Enough query rows per kv head for the kernel whose wavefronts share K/V tiles (GQA group of 8 and
+    79 rows: 40 tiles), and a count that fills its blocks of 8 tiles too badly (66 rows: 33 tiles)."""
+    shape = D.AttnUpdateShape(batch=16, n_q_heads=128, n_kv_heads=16, seq_len=300, head_dim=128, dtype=BF16)
+    _attn_case(shape, 79, 36)
+    _attn_case(shape, 66, 37)
+
+
 def test_attention_generic_paths():
     _attn_case(D.AttnUpdateShape(batch=2, n_q_heads=4, n_kv_heads=4, seq_len=70, head_dim=32, dtype=FP32),
                None, 41, ragged=[9, 33])
