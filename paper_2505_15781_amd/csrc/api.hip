@@ -384,7 +384,8 @@ extern "C" int dkv_denoise_step(dkv_ctx *c, int32_t step, const int32_t *forced_
                    (2.0 * r.batch * m.n_kv_heads * c->L + 2.0 * rows * m.n_q_heads) * m.head_dim * (double)c->es,
                    4.0 * rows * m.n_q_heads * (double)c->L * m.head_dim, [&] {
                        return dkv_launch_attention(dt, c->q, Kl, Vl, c->row_off, c->attn_out, r.batch, m.n_q_heads,
-                                                   m.n_kv_heads, c->L, m.head_dim, rows, ap, c->attn_part, s);
+                                                   m.n_kv_heads, c->L, m.head_dim, rows, ap, c->attn_part,
+                                                   AttnFusedUpdate{nullptr, nullptr, nullptr}, s);
                    });
         if (rc) return rc;
         p = dkv_gemm_plan(dt, rows, d, qn);
@@ -558,11 +559,15 @@ extern "C" int dkv_attn_update(void *k_cache, void *v_cache, const void *q, cons
         return DKV_E_WORKSPACE_TOO_SMALL;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // few rows per sequence: the attention kernel writes the new rows into the cache itself
+    if (dkv_attn_can_fuse_update(p, max_rows_per_seq))
+        return dkv_launch_attention(dtype, q, k_cache, v_cache, active_off, out, batch, n_q_heads, n_kv_heads,
+                                    seq_len, head_dim, rows, p, workspace, AttnFusedUpdate{k_new, v_new, active_idx}, s);
     int rc = dkv_launch_scatter_rows(dtype, s, rows, k_new, v_new, active_idx, active_off, k_cache, v_cache, batch,
                                      n_kv_heads, seq_len, head_dim);
     if (rc) return rc;
     return dkv_launch_attention(dtype, q, k_cache, v_cache, active_off, out, batch, n_q_heads, n_kv_heads, seq_len,
-                                head_dim, rows, p, workspace, s);
+                                head_dim, rows, p, workspace, AttnFusedUpdate{nullptr, nullptr, nullptr}, s);
 }
 
 extern "C" size_t dkv_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t dtype) {

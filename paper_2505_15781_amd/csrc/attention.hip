@@ -20,15 +20,29 @@ namespace {
 constexpr int KT = 32;                 // keys per tile
 
 template <int DH> struct AttnSmem {
-    static constexpr int K_STRIDE = DH * 2 + 16;        // bytes per key row (+16 spreads banks)
-    static constexpr int VT_STRIDE = KT * 2 + 8;        // bytes per head-dim row of V^T
+    static constexpr int K_STRIDE = DH * 2 + 16;        // bytes per K row (+16 spreads the 16-byte fragment reads)
+    static constexpr int V_STRIDE = DH * 2 + 32;        // bytes per V row (+32 spreads the transposing reads)
     static constexpr int K_BYTES = KT * K_STRIDE;
-    static constexpr int VT_BYTES = DH * VT_STRIDE;
-    static constexpr int WAVE_BYTES = K_BYTES + VT_BYTES;
+    static constexpr int V_BYTES = KT * V_STRIDE;
+    static constexpr int WAVE_BYTES = K_BYTES + V_BYTES;
 };
 
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((address_space(3))) bf16x4 *lds_bf16x4_ptr;
+
+// MFMA operand V^T[dim 16 mt + (lane & 15)][8 keys] from V rows stored as they are in the cache (row = key).
+// ds_read_b64_tr_b16 works on blocks of 16 lanes: lane j points at 4 consecutive 16-bit elements, and lane i
+// receives element i % 4 of the pieces of lanes i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12. With lane j pointing
+// at dims [16 mt + 4 (j % 4), +4) of key j / 4, lane i gets dim 16 mt + i of four consecutive keys. Two reads
+// give the 8 keys of the lane's K group in the order the probabilities come out of the score MFMA:
+// keys key0 + 4 g + {0..3} and key0 + 16 + 4 g + {0..3}, g = lane / 16. `vrow0` = address of (key 4 g + j / 4,
+// dim 4 (j % 4)) of the tile, precomputed per lane.
+__device__ __forceinline__ bf16x8 vt_operand(const unsigned char *vrow0, int mt, int v_stride, int key0) {
+    const unsigned char *a = vrow0 + key0 * v_stride + mt * 32;
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(a));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(a + 16 * v_stride));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
 
 // One online-softmax step of a lane over NT sub-tiles of 16 keys (Eq. 4's softmax, streamed): st[jt][i] is the raw
 // score of key key_base + 16 jt + i against this lane's query. Updates the running max (log2 domain) and sum,
@@ -38,19 +52,30 @@ template <int NT, int NACC>
 __device__ __forceinline__ void softmax_step(f32x4 (&st)[NT], float &m_run, float &l_run, f32x4 (&acc)[NACC],
                                              bf16x8 (&pb)[NT / 2], int key_base, int L, bool masked,
                                              float scale_log2e) {
+    if (masked) {              // wave-uniform: only the last tile of a sequence has keys past the end
+#pragma unroll
+        for (int jt = 0; jt < NT; ++jt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (key_base + 16 * jt + i >= L) st[jt][i] = -INFINITY;
+    }
     float mx = -INFINITY;
 #pragma unroll
     for (int jt = 0; jt < NT; ++jt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (masked && key_base + 16 * jt + i >= L) st[jt][i] = -INFINITY;
-            mx = fmaxf(mx, st[jt][i]);
-        }
+        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, st[jt][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx * scale_log2e);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
+    // Rescale only when some query of the wavefront got a new maximum (rare after the first tiles): for the
+    // others the factor would be exactly 1.
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+#pragma unroll
+        for (int mt = 0; mt < NACC; ++mt) acc[mt] *= alpha;
+        m_run = m_new;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int hh = 0; hh < NT / 2; ++hh) {
@@ -62,9 +87,7 @@ __device__ __forceinline__ void softmax_step(f32x4 (&st)[NT], float &m_run, floa
         }
         pb[hh] = __builtin_convertvector(p, bf16x8);
     }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int mt = 0; mt < NACC; ++mt) acc[mt] *= alpha;
+    l_run += psum;
 }
 
 #include "attn_shared.h"
@@ -192,12 +215,12 @@ AttnPlan dkv_attn_plan(int dtype, int batch, int n_q_heads, int n_kv_heads, int 
         p.tiles_per_split = ceil_div(seq_len, KT);
         return p;
     }
-    // Measured on MI355X over the shapes of the four workloads: the key-split kernel wins unless there are
-    // many query tiles per kv head that fill the shared kernel's blocks of 8 tiles well and enough blocks to
-    // occupy the chip without slicing the keys (then the shared K/V tiles save L2 traffic and staging work).
+    // Measured on MI355X over the shapes of the four workloads: the shared-tile kernel (about 450 TFLOP/s when
+    // compute bound, against 200 for the key-split kernel, and K/V read from L2 once per 128 query rows) wins
+    // as soon as its blocks of 8 query tiles make enough workgroups to occupy the chip without slicing the
+    // keys, even when the last block of a head is mostly empty; below that the key-split kernel does.
     const int blocks8 = ceil_div(p.q_tiles, 8);
-    const bool shared = head_dim == 128 && p.q_tiles >= 16 && (long)batch * n_kv_heads * blocks8 >= 256 &&
-                        (blocks8 * 8 - p.q_tiles) * 10 <= p.q_tiles;
+    const bool shared = head_dim == 128 && p.q_tiles >= 5 && (long)batch * n_kv_heads * blocks8 >= 192;
     int s = 1, n_tiles, min_tiles;
     if (shared) {
         p.shared_nq = 2;
@@ -230,11 +253,18 @@ size_t dkv_attn_partial_bytes(const AttnPlan &p, int batch, int n_q_heads, int n
     return rows * n_q_heads * p.splits * (size_t)(head_dim + 4) * sizeof(float);
 }
 
-int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const void *v_cache,
-                         const int *row_off, void *out, int batch, int n_q_heads, int n_kv_heads,
-                         int seq_len, int head_dim, int rows_upper, AttnPlan plan, void *partial,
-                         hipStream_t stream) {
+int dkv_attn_can_fuse_update(const AttnPlan &plan, int max_rows_per_seq) {
+    return plan.use_mfma && plan.ksplit_nq > 0 && max_rows_per_seq <= 64;
+}
+
+int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache, const int *row_off, void *out,
+                         int batch, int n_q_heads, int n_kv_heads, int seq_len, int head_dim, int rows_upper,
+                         AttnPlan plan, void *partial, AttnFusedUpdate fuse, hipStream_t stream) {
     if (rows_upper <= 0) return DKV_OK;
+    if (fuse.k_new && !plan.ksplit_nq) {
+        dkv_set_error("the cache update can only be fused into the key-split attention kernel");
+        return DKV_E_INVALID_ARG;
+    }
     if (!plan.use_mfma) {
         if (dtype == DKV_BF16)
             return launch_generic<bf16_t>(q, k_cache, v_cache, row_off, out, batch, n_q_heads, n_kv_heads,
@@ -246,19 +276,25 @@ int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const vo
     long pairs = (long)rows_upper * n_q_heads;
     if (plan.ksplit_nq) {
         const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_groups * plan.splits);
-#define KSPLIT(D, NQ, NW)                                                                                      \
+#define KSPLIT_F(D, NQ, NW, F)                                                                                 \
     do {                                                                                                       \
         static bool lds_ok = false;                                                                            \
         const size_t smem = NW * AttnSmem<D>::WAVE_BYTES;                                                      \
         if (!lds_ok) {                                                                                         \
-            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_ksplit<D, NQ, NW>),      \
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_ksplit<D, NQ, NW, F>),   \
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));           \
             lds_ok = true;                                                                                     \
         }                                                                                                      \
-        hipLaunchKernelGGL((attn_bf16_ksplit<D, NQ, NW>), dim3(wgs), dim3(64 * NW), smem, stream,              \
-                           (const bf16_t *)q, (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off,       \
-                           (bf16_t *)out, (float *)partial, batch, n_q_heads, n_kv_heads, seq_len,             \
-                           plan.q_groups, plan.splits, plan.tiles_per_split, rows_upper, scale_log2e);         \
+        hipLaunchKernelGGL((attn_bf16_ksplit<D, NQ, NW, F>), dim3(wgs), dim3(64 * NW), smem, stream,           \
+                           (const bf16_t *)q, (bf16_t *)k_cache, (bf16_t *)v_cache, row_off, (bf16_t *)out,    \
+                           (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_groups,             \
+                           plan.splits, plan.tiles_per_split, rows_upper, scale_log2e,                         \
+                           (const bf16_t *)fuse.k_new, (const bf16_t *)fuse.v_new, fuse.active_idx);           \
+    } while (0)
+#define KSPLIT(D, NQ, NW)                                                                                      \
+    do {                                                                                                       \
+        if (fuse.k_new) KSPLIT_F(D, NQ, NW, true);                                                             \
+        else KSPLIT_F(D, NQ, NW, false);                                                                       \
     } while (0)
         if (head_dim == 128) {
             if (plan.ksplit_waves == 8) {
@@ -277,6 +313,7 @@ int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const vo
                 else KSPLIT(64, 1, 4);
             }
         }
+#undef KSPLIT_F
 #undef KSPLIT
         DKV_LAUNCH_CHECK();
         if (plan.splits > 1) {
@@ -291,30 +328,18 @@ int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const vo
             DKV_LAUNCH_CHECK();
         }
     } else if (plan.shared_nq) {
-        const size_t smem = 2 * (64 * (128 * 2 + 16) + 128 * (64 * 2 + 8));
+        const size_t smem = 2 * 64 * ((128 * 2 + 16) + (128 * 2 + 32));   // two stages of 64 K rows and 64 V rows
         const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_blocks * plan.splits);
-        static bool lds_ok1 = false, lds_ok2 = false;
-        if (plan.shared_nq == 1) {
-            if (!lds_ok1) {
-                DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-                lds_ok1 = true;
-            }
-            hipLaunchKernelGGL((attn_bf16_shared<1>), dim3(wgs), dim3(256), smem, stream, (const bf16_t *)q,
-                               (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out,
-                               (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits,
-                               plan.tiles_per_split, rows_upper, scale_log2e);
-        } else {
-            if (!lds_ok2) {
-                DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-                lds_ok2 = true;
-            }
-            hipLaunchKernelGGL((attn_bf16_shared<2>), dim3(wgs), dim3(256), smem, stream, (const bf16_t *)q,
-                               (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out,
-                               (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits,
-                               plan.tiles_per_split, rows_upper, scale_log2e);
+        static bool lds_ok = false;
+        if (!lds_ok) {
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            lds_ok = true;
         }
+        hipLaunchKernelGGL((attn_bf16_shared<2>), dim3(wgs), dim3(256), smem, stream, (const bf16_t *)q,
+                           (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out,
+                           (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits,
+                           plan.tiles_per_split, rows_upper, scale_log2e);
         DKV_LAUNCH_CHECK();
         if (plan.splits > 1) {
             hipLaunchKernelGGL((attn_merge<128>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream,

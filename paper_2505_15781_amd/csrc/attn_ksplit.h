@@ -3,20 +3,27 @@
 //
 // Work item = (sequence, kv head, group of NQ query tiles of 16 rows, key slice). The workgroup's key
 // tiles (32 keys each) are dealt round-robin to its wavefronts; every wavefront streams its tiles through a
-// private LDS region exactly as attn_bf16_mfma does (K rows and transposed V, next tile's global loads in
-// flight during the products) and keeps an online softmax for its NQ query tiles. At the end the NW
+// private LDS region (K and V rows as stored; the V operand of the second product comes out of LDS through
+// transposing reads; the next tile's global loads are in flight during the products) and keeps an online softmax for its NQ query tiles. At the end the NW
 // (max, sum, unnormalised output) states meet in LDS and are merged there, so with one key slice per item the
 // normalised bf16 output is written directly: no partial records in global memory and no merge launch. With
 // several key slices the merged state of the workgroup is one partial record (a quarter of what one record
 // per wavefront would need) for attn_merge.
+//
+// FUSE: the cache update of the step (Eq. 4: the rows of M_{t-1} are replaced by the freshly computed ones)
+// happens inside this kernel instead of in a launch before it. Every lane holds one active position of the
+// sequence (at most 64 rows per sequence); after a tile of cache rows has been staged in LDS, the tile's
+// active rows are overwritten there with the new K/V rows, and the workgroups of query group 0 also write
+// them to the cache in global memory. Workgroups that read such a row from global memory while it is being
+// written replace it in LDS anyway, so no ordering between workgroups is needed.
 #pragma once
 
-template <int DH, int NQ, int NW>
+template <int DH, int NQ, int NW, bool FUSE>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
-    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
-    const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
-    int Hq, int Hkv, int L, int q_groups, int splits, int tiles_per_split, int rows_cap,
-    float scale_log2e) {
+    const bf16_t *__restrict__ Q, bf16_t *Kc, bf16_t *Vc, const int *__restrict__ row_off,
+    bf16_t *__restrict__ out, float *__restrict__ part, int batch, int Hq, int Hkv, int L, int q_groups,
+    int splits, int tiles_per_split, int rows_cap, float scale_log2e, const bf16_t *__restrict__ k_new,
+    const bf16_t *__restrict__ v_new, const int *__restrict__ active_idx) {
     using SM = AttnSmem<DH>;
     constexpr int REC = DH + 4;                       // floats per merged row: m, l, pad, pad, o[DH]
     static_assert(NQ * 16 * REC * 4 <= SM::WAVE_BYTES, "merge records fit the wavefront's LDS region");
@@ -53,55 +60,47 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
         }
     }
 
-    const bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
-    const bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    int my_pos = -1;                             // FUSE: active position number `lane` of this sequence
+    if (FUSE && lane < nrows && r0 + lane < rows_cap) my_pos = active_idx[r0 + lane];
     const int n_tiles = (L + KT - 1) / KT;
     const int t_begin = split * tiles_per_split, t_end = min(n_tiles, t_begin + tiles_per_split);
 
-    constexpr int KCH = KT * DH / 8 / 64;             // 16-byte K chunks per lane
-    constexpr int VTASK = (KT / 4) * (DH / 8) / 64;   // (4 keys x 8 dims) transposition tasks per lane
-    uint4 kreg[KCH], vreg[VTASK][4];
+    constexpr int KCH = KT * DH / 8 / 64;             // 16-byte chunks of K (and of V) per lane
+    uint4 kreg[KCH], vreg[KCH];
+    // chunk i of a lane: key lane / (DH/8) + i * 64 / (DH/8) of the tile, dims [8 (lane % (DH/8)), +8)
+    constexpr int ROWS_PER_I = 64 / (DH / 8);
+    const int lane_off = (lane / (DH / 8)) * DH + (lane % (DH / 8)) * 8;
     auto load_tile = [&](int t) {
-        const int key0 = t * KT;
+        const size_t base = (size_t)t * KT * DH;               // wave-uniform
+        const bf16_t *kt = Kb + base + lane_off, *vt = Vb + base + lane_off;
+        if ((t + 1) * KT <= L) {
 #pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            const int c = lane + 64 * i, key = c / (DH / 8), ch = c % (DH / 8), gk = key0 + key;
-            kreg[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
-        }
+            for (int i = 0; i < KCH; ++i) {
+                kreg[i] = *reinterpret_cast<const uint4 *>(kt + i * ROWS_PER_I * DH);
+                vreg[i] = *reinterpret_cast<const uint4 *>(vt + i * ROWS_PER_I * DH);
+            }
+        } else {
+            const int key = t * KT + lane / (DH / 8);
 #pragma unroll
-        for (int i = 0; i < VTASK; ++i) {
-            const int task = lane + 64 * i, dc = task % (DH / 8), kg = task / (DH / 8);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int gk = key0 + 4 * kg + j;
-                vreg[i][j] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + dc * 8)
-                                    : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < KCH; ++i) {
+                const bool ok = key + i * ROWS_PER_I < L;
+                kreg[i] = ok ? *reinterpret_cast<const uint4 *>(kt + i * ROWS_PER_I * DH) : make_uint4(0, 0, 0, 0);
+                vreg[i] = ok ? *reinterpret_cast<const uint4 *>(vt + i * ROWS_PER_I * DH) : make_uint4(0, 0, 0, 0);
             }
         }
     };
+    unsigned char *k_dst = ksm + (lane / (DH / 8)) * SM::K_STRIDE + (lane % (DH / 8)) * 16;
+    unsigned char *v_dst = vsm + (lane / (DH / 8)) * SM::V_STRIDE + (lane % (DH / 8)) * 16;
     auto store_tile = [&]() {
 #pragma unroll
         for (int i = 0; i < KCH; ++i) {
-            const int c = lane + 64 * i, key = c / (DH / 8), ch = c % (DH / 8);
-            *reinterpret_cast<uint4 *>(ksm + key * SM::K_STRIDE + ch * 16) = kreg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < VTASK; ++i) {
-            const int task = lane + 64 * i, dc = task % (DH / 8), kg = task / (DH / 8);
-            const uint32_t *v0 = reinterpret_cast<const uint32_t *>(&vreg[i][0]);
-            const uint32_t *v1 = reinterpret_cast<const uint32_t *>(&vreg[i][1]);
-            const uint32_t *v2 = reinterpret_cast<const uint32_t *>(&vreg[i][2]);
-            const uint32_t *v3 = reinterpret_cast<const uint32_t *>(&vreg[i][3]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {     // word e holds dims 2e (low half) and 2e+1 (high half)
-                const uint2 lo = make_uint2(pack_lo(v0[e], v1[e]), pack_lo(v2[e], v3[e]));
-                const uint2 hi = make_uint2(pack_hi(v0[e], v1[e]), pack_hi(v2[e], v3[e]));
-                const int d = dc * 8 + 2 * e;
-                *reinterpret_cast<uint2 *>(vsm + d * SM::VT_STRIDE + kg * 8) = lo;
-                *reinterpret_cast<uint2 *>(vsm + (d + 1) * SM::VT_STRIDE + kg * 8) = hi;
-            }
+            *reinterpret_cast<uint4 *>(k_dst + i * ROWS_PER_I * SM::K_STRIDE) = kreg[i];
+            *reinterpret_cast<uint4 *>(v_dst + i * ROWS_PER_I * SM::V_STRIDE) = vreg[i];
         }
     };
+    const unsigned char *vrow0 = vsm + (4 * g + (qi >> 2)) * SM::V_STRIDE + (qi & 3) * 8;
 
     float m_run[NQ], l_run[NQ];
     f32x4 acc[NQ][DH / 16];
@@ -120,6 +119,23 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         store_tile();
+        if (FUSE) {
+            unsigned long long hit = __ballot(my_pos >= t * KT && my_pos < (t + 1) * KT);
+            while (hit) {                                    // wave-uniform: rows of this tile that are replaced
+                const int src = __ffsll(hit) - 1;
+                hit &= hit - 1;
+                const int p = __shfl(my_pos, src, 64);
+                if (lane < 2 * (DH / 8)) {                   // 16-byte chunks: first the K row, then the V row
+                    const bool is_v = lane >= DH / 8;
+                    const int ch = lane % (DH / 8);
+                    const size_t row = ((size_t)(r0 + src) * Hkv + kvh) * DH + ch * 8;
+                    const uint4 v = *reinterpret_cast<const uint4 *>((is_v ? v_new : k_new) + row);
+                    *reinterpret_cast<uint4 *>((is_v ? vsm + (p - t * KT) * SM::V_STRIDE
+                                                     : ksm + (p - t * KT) * SM::K_STRIDE) + ch * 16) = v;
+                    if (qg == 0) *reinterpret_cast<uint4 *>((is_v ? Vb : Kb) + (size_t)p * DH + ch * 8) = v;
+                }
+            }
+        }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         if (t + NW < t_end) load_tile(t + NW);
@@ -146,14 +162,10 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
                                      scale_log2e);
 #pragma unroll
         for (int mt = 0; mt < DH / 16; ++mt) {
-            const unsigned char *vrow = vsm + (16 * mt + qi) * SM::VT_STRIDE;
-            const uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + g * 8);          // keys 4g..4g+3
-            const uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 + g * 8);     // keys 16+4g..
-            uint4 av = make_uint4(a0.x, a0.y, a1.x, a1.y);
+            const bf16x8 av = vt_operand(vrow0, mt, SM::V_STRIDE, 0);
 #pragma unroll
             for (int j = 0; j < NQ; ++j)
-                acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&av), pb[j][0],
-                                                                     acc[j][mt], 0, 0, 0);
+                acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[j][0], acc[j][mt], 0, 0, 0);
         }
     }
 

@@ -3,22 +3,22 @@
 //
 // Work item = (sequence, kv head, block of 4*NQ query tiles of 16 rows, key slice). The workgroup
 // streams its key slice in tiles of 64 keys: every thread fetches part of the K rows and of the V rows
-// (the latter transposed on the way into LDS), two LDS stages alternate, and the next tile's global
+// as they are stored (transposing LDS reads form the V operand of the second product), two LDS stages alternate, and the next tile's global
 // loads are in flight while the current one is multiplied. Each wavefront multiplies its own NQ query
 // tiles against the shared tile, so a K or V fragment read from LDS feeds NQ MFMAs and the tile is read
 // from L2 once per 64*NQ query rows instead of once per 16.
 #pragma once
 
 template <int NQ>
-__global__ __launch_bounds__(256) void attn_bf16_shared(
+__global__ __launch_bounds__(256, 2) void attn_bf16_shared(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
     const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
     int Hq, int Hkv, int L, int q_blocks, int splits, int tiles_per_split, int rows_cap,
     float scale_log2e) {
     constexpr int DH = 128, KT2 = 64;
     constexpr int K_STRIDE = DH * 2 + 16;      // bytes per key row
-    constexpr int VT_STRIDE = KT2 * 2 + 8;     // bytes per head-dim row of V^T
-    constexpr int K_BYTES = KT2 * K_STRIDE, STAGE_BYTES = K_BYTES + DH * VT_STRIDE;
+    constexpr int V_STRIDE = DH * 2 + 32;      // bytes per V row
+    constexpr int K_BYTES = KT2 * K_STRIDE, STAGE_BYTES = K_BYTES + KT2 * V_STRIDE;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -58,20 +58,15 @@ __global__ __launch_bounds__(256) void attn_bf16_shared(
     const int n_tiles = (L + KT2 - 1) / KT2;
     const int t0 = split * tiles_per_split, t1 = min(n_tiles, t0 + tiles_per_split);
 
-    // per thread: 4 K chunks (16 B) and one 4-key x 8-dim block of V
+    // per thread: 4 chunks (16 B) of K and of V
     uint4 kreg[4], vreg[4];
-    const int v_dc = tid & 15, v_kg = tid >> 4;
     auto load_tile = [&](int t) {
         const int key0 = t * KT2;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int c = tid + 256 * i, key = c >> 4, ch = c & 15, gk = key0 + key;
             kreg[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int gk = key0 + 4 * v_kg + j;
-            vreg[j] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + v_dc * 8) : make_uint4(0, 0, 0, 0);
+            vreg[i] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
         }
     };
     auto store_tile = [&](int stage) {
@@ -80,20 +75,10 @@ __global__ __launch_bounds__(256) void attn_bf16_shared(
         for (int i = 0; i < 4; ++i) {
             const int c = tid + 256 * i, key = c >> 4, ch = c & 15;
             *reinterpret_cast<uint4 *>(ksm + key * K_STRIDE + ch * 16) = kreg[i];
-        }
-        const uint32_t *v0 = reinterpret_cast<const uint32_t *>(&vreg[0]);
-        const uint32_t *v1 = reinterpret_cast<const uint32_t *>(&vreg[1]);
-        const uint32_t *v2 = reinterpret_cast<const uint32_t *>(&vreg[2]);
-        const uint32_t *v3 = reinterpret_cast<const uint32_t *>(&vreg[3]);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {      // word e holds dims 2e (low half) and 2e+1 (high half)
-            const uint2 lo = make_uint2(pack_lo(v0[e], v1[e]), pack_lo(v2[e], v3[e]));
-            const uint2 hi = make_uint2(pack_hi(v0[e], v1[e]), pack_hi(v2[e], v3[e]));
-            const int d = v_dc * 8 + 2 * e;
-            *reinterpret_cast<uint2 *>(vsm + d * VT_STRIDE + v_kg * 8) = lo;
-            *reinterpret_cast<uint2 *>(vsm + (d + 1) * VT_STRIDE + v_kg * 8) = hi;
+            *reinterpret_cast<uint4 *>(vsm + key * V_STRIDE + ch * 16) = vreg[i];
         }
     };
+    const int v_lane_off = (4 * g + (qi >> 2)) * V_STRIDE + (qi & 3) * 8;
 
     float m_run[NQ], l_run[NQ];
     f32x4 acc[NQ][DH / 16];
@@ -140,14 +125,10 @@ __global__ __launch_bounds__(256) void attn_bf16_shared(
         for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
             for (int mt = 0; mt < DH / 16; ++mt) {
-                const unsigned char *vrow = vsm + (16 * mt + qi) * VT_STRIDE + 64 * hh;
-                const uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + g * 8);          // keys 4g..4g+3
-                const uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 + g * 8);     // keys 16+4g..
-                uint4 av = make_uint4(a0.x, a0.y, a1.x, a1.y);
+                const bf16x8 av = vt_operand(vsm + v_lane_off, mt, V_STRIDE, 32 * hh);
 #pragma unroll
                 for (int j = 0; j < NQ; ++j)
-                    acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&av), pb[j][hh],
-                                                                         acc[j][mt], 0, 0, 0);
+                    acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[j][hh], acc[j][mt], 0, 0, 0);
             }
         if (t + 1 < t1) store_tile(stage ^ 1);
         __syncthreads();

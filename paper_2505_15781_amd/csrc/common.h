@@ -105,8 +105,15 @@ AttnPlan dkv_attn_plan(int dtype, int batch, int n_q_heads, int n_kv_heads, int 
                        int max_rows_per_seq);
 size_t dkv_attn_partial_bytes(const AttnPlan &p, int batch, int n_q_heads, int n_kv_heads, int head_dim);
 
+// New K/V rows that the attention kernel itself writes into the cache before using them (all null: the cache
+// is already up to date). Row r holds [n_kv_heads][head_dim] for position active_idx[r] of its sequence.
+struct AttnFusedUpdate {
+    const void *k_new, *v_new;
+    const int *active_idx;
+};
+int dkv_attn_can_fuse_update(const AttnPlan &plan, int max_rows_per_seq);
+
 // out[r, h, :] = attention of q[r, h] over all seq_len positions of sequence b(r).
-int dkv_launch_attention(int dtype, const void *q, const void *k_cache, const void *v_cache,
-                         const int *row_off, void *out, int batch, int n_q_heads, int n_kv_heads,
-                         int seq_len, int head_dim, int rows_upper, AttnPlan plan, void *partial,
-                         hipStream_t stream);
+int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache, const int *row_off, void *out,
+                         int batch, int n_q_heads, int n_kv_heads, int seq_len, int head_dim, int rows_upper,
+                         AttnPlan plan, void *partial, AttnFusedUpdate fuse, hipStream_t stream);

@@ -140,10 +140,19 @@ def test_attention_key_slices_across_workgroups(dh):
 
 def test_attention_many_query_tiles_per_head():
     """Enough query rows per kv head for the kernel whose wavefronts share K/V tiles (GQA group of 8 and
-    79 rows: 40 tiles), and a count that fills its blocks of 8 tiles too badly (66 rows: 33 tiles)."""
+    79 rows: 40 tiles = 5 full blocks of 8), and a count that leaves its last block almost empty (66 rows:
+    33 tiles)."""
     shape = D.AttnUpdateShape(batch=16, n_q_heads=128, n_kv_heads=16, seq_len=300, head_dim=128, dtype=BF16)
     _attn_case(shape, 79, 36)
     _attn_case(shape, 66, 37)
+
+
+@pytest.mark.parametrize("dh", [128, 64])
+def test_attention_many_small_items(dh):
+    """More (sequence, head, query group) items than compute units: the key-split kernel in its
+    4-wavefront form, two workgroups per compute unit, with the cache update fused (40 rows per sequence)."""
+    shape = D.AttnUpdateShape(batch=20, n_q_heads=16, n_kv_heads=16, seq_len=150, head_dim=dh, dtype=BF16)
+    _attn_case(shape, 40, 38)
 
 
 def test_attention_generic_paths():
