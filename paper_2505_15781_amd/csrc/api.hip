@@ -52,6 +52,7 @@ bool model_ok(const dkv_model_desc &m) {
 struct Layout {
     size_t rope, row_pos, row_seq, row_off, cand_row, cand_pos, cand_off, counts, cand_tok, cand_conf, taken,
         d_prev, status, h, a, q, attn_out, f, a_c, logits, part, attn_part, total;
+    size_t head_part;
     size_t part_floats, attn_part_bytes;
     int rows_cap, cand_cap;
 };
@@ -120,6 +121,7 @@ Layout make_layout(const dkv_model_desc &m, const dkv_run_desc &r) {
     y.f = take((size_t)y.rows_cap * m.d_ffn * es);
     y.a_c = take((size_t)y.cand_cap * m.d_model * es);
     y.logits = take((size_t)y.cand_cap * m.vocab * 4);
+    y.head_part = take(dkv_head_stats_scratch_bytes(y.cand_cap));
     y.part = take(y.part_floats * 4);
     y.attn_part = take(y.attn_part_bytes);
     y.total = o;
@@ -145,7 +147,7 @@ struct dkv_ctx {
     int *row_pos, *row_seq, *row_off, *cand_row, *cand_pos, *cand_off, *counts, *cand_tok, *d_prev, *status;
     float *cand_conf, *h, *logits, *part;
     uint8_t *taken;
-    void *a, *q, *attn_out, *f, *a_c, *attn_part;
+    void *a, *q, *attn_out, *f, *a_c, *attn_part, *head_part;
     // step state (host)
     int next_step, selected_step, forced_scope;
     int rows_upper, rows_per_seq_upper, cand_upper;
@@ -297,6 +299,7 @@ extern "C" int dkv_init_cache(dkv_ctx **out, const dkv_model_desc *model, const 
     c->h = ws<float>(c, lay.h); c->a = ws<void>(c, lay.a); c->q = ws<void>(c, lay.q);
     c->attn_out = ws<void>(c, lay.attn_out); c->f = ws<void>(c, lay.f); c->a_c = ws<void>(c, lay.a_c);
     c->logits = ws<float>(c, lay.logits); c->part = ws<float>(c, lay.part); c->attn_part = ws<void>(c, lay.attn_part);
+    c->head_part = ws<void>(c, lay.head_part);
     c->next_step = 0; c->selected_step = -1; c->forced_scope = -1;
     c->rows_upper = c->cand_upper = c->last_rows_upper = c->last_cand_upper = 0;
 
@@ -411,7 +414,8 @@ extern "C" int dkv_denoise_step(dkv_ctx *c, int32_t step, const int32_t *forced_
         if ((rc = timed_gemm(c, c->a_c, c->lm_head, c->part, cands, n_cand, m.vocab, d, hp))) return rc;
         if ((rc = dkv_launch_reduce_partials(s, c->part, hp.split_k, (size_t)cands * m.vocab, lg, (size_t)cands * m.vocab))) return rc;
     }
-    if ((rc = dkv_launch_head_stats(s, cands, lg, c->counts, m.vocab, m.mask_id, c->cand_tok, c->cand_conf, c->status))) return rc;
+    if ((rc = dkv_launch_head_stats(s, cands, lg, c->counts, m.vocab, m.mask_id, c->cand_tok, c->cand_conf, c->status,
+                                    c->head_part))) return rc;
 
     CommitArgs ca;
     ca.cand_off = c->cand_off; ca.cand_pos = c->cand_pos; ca.cand_tok = c->cand_tok; ca.cand_conf = c->cand_conf;

@@ -49,8 +49,10 @@ int dkv_launch_gather_rows(int dtype, hipStream_t s, int cands, const void *src,
                            const int *counts, void *dst, int d);
 int dkv_launch_reduce_partials(hipStream_t s, const float *part, int splits, size_t stride, float *out,
                                size_t total);
+constexpr int HEAD_SLICES = 16;     // vocabulary ranges per candidate row in the head statistics
+size_t dkv_head_stats_scratch_bytes(int cands);
 int dkv_launch_head_stats(hipStream_t s, int cands, const float *logits, const int *counts, int V,
-                          int mask_id, int *tok, float *conf, int *status);
+                          int mask_id, int *tok, float *conf, int *status, void *scratch);
 int dkv_launch_commit(const CommitArgs &a, hipStream_t s);
 int dkv_launch_init_state(hipStream_t s, int *tokens, uint8_t *masked, int *stamp, int *d_prev, int *status,
                           int batch, int L, int P, int k, int mask_id);

@@ -274,46 +274,94 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
 // Per candidate row: token = arg max of the logits with MASK excluded (lowest id on ties),
 // confidence = its softmax probability (Sec. 3.1: keep the most confident predictions).
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void head_stats_kernel(const float *__restrict__ logits,
-                                                          const int *__restrict__ counts, int V, int mask_id,
-                                                          int *__restrict__ tok, float *__restrict__ conf,
-                                                          int *__restrict__ status) {
-    __shared__ float smax[16];
-    __shared__ int sidx[16];
-    __shared__ float red[16];
-    const int c = blockIdx.x;
+// Two kernels: the vocabulary is cut into HEAD_SLICES ranges so that a handful of candidate rows still
+// occupies the chip; every (row, range) block makes one pass keeping a running (max, sum of exp, arg max),
+// the second kernel merges the ranges of a row.
+struct HeadPartial {
+    float max, sum;     // sum of exp(x - max) over the range
+    int idx, nan;
+};
+
+__device__ __forceinline__ void head_merge(float &m, float &s, int &i, float om, float os, int oi) {
+    if (om > m || (om == m && oi < i)) {
+        s = s * expf(m - om) + os;       // m == -inf only with s == 0: exp(-inf) * 0 is never formed as inf * 0
+        m = om;
+        i = oi;
+    } else if (om > -INFINITY) {
+        s += os * expf(om - m);
+    }
+}
+
+__global__ __launch_bounds__(256) void head_stats_partial_kernel(const float *__restrict__ logits,
+                                                                 const int *__restrict__ counts, int V,
+                                                                 int mask_id, HeadPartial *__restrict__ part) {
+    __shared__ float sm[4], ss[4];
+    __shared__ int si[4], sn[4];
+    const int c = blockIdx.y, slice = blockIdx.x;
     if (c >= counts[1]) return;
+    const int per = ((V + HEAD_SLICES - 1) / HEAD_SLICES + 3) & ~3;      // multiple of 4: aligned float4 loads
+    const int v0 = slice * per, v1 = min(V, v0 + per);
     const float *row = logits + (size_t)c * V;
-    float best = -INFINITY;
+    float m = -INFINITY, sum = 0.f;
     int bi = 0x7fffffff;
     bool nan = false;
-    for (int v = threadIdx.x; v < V; v += blockDim.x) {
-        if (v == mask_id) continue;
-        float x = row[v];
+    auto take = [&](float x, int v) {
+        if (v == mask_id) return;
         nan |= (x != x);
-        if (x > best) { best = x; bi = v; }      // ascending v per thread: first max wins
+        if (x > m) {                     // ascending v per thread: the first maximum wins
+            sum = sum * expf(m - x) + 1.f;
+            m = x;
+            bi = v;
+        } else {
+            sum += expf(x - m);
+        }
+    };
+    const bool vec = ((size_t)c * V) % 4 == 0;          // row start 16-byte aligned
+    if (vec) {
+        for (int v = v0 + 4 * threadIdx.x; v < v1; v += 4 * 256) {
+            if (v + 3 < v1) {
+                const float4 x = *reinterpret_cast<const float4 *>(row + v);
+                take(x.x, v); take(x.y, v + 1); take(x.z, v + 2); take(x.w, v + 3);
+            } else {
+                for (int u = v; u < v1; ++u) take(row[u], u);
+            }
+        }
+    } else {
+        for (int v = v0 + threadIdx.x; v < v1; v += 256) take(row[v], v);
     }
-    // wave then block reduction of (value, lowest index)
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float ob = __shfl_xor(best, o, 64);
-        int oi = __shfl_xor(bi, o, 64);
-        if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
-    }
-    const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    if ((threadIdx.x & 63) == 0) { smax[w] = best; sidx[w] = bi; }
-    if (__syncthreads_or(nan) && threadIdx.x == 0) atomicOr(status, STATUS_NAN);
-    best = smax[0]; bi = sidx[0];
-    for (int i = 1; i < nw; ++i)
-        if (smax[i] > best || (smax[i] == best && sidx[i] < bi)) { best = smax[i]; bi = sidx[i]; }
-    float se = 0.f;
-    for (int v = threadIdx.x; v < V; v += blockDim.x)
-        if (v != mask_id) se += expf(row[v] - best);
-    se = block_sum(se, red);
+    for (int o = 32; o > 0; o >>= 1)
+        head_merge(m, sum, bi, __shfl_xor(m, o, 64), __shfl_xor(sum, o, 64), __shfl_xor(bi, o, 64));
+    const int w = threadIdx.x >> 6;
+    const bool any_nan = __any(nan);
+    if ((threadIdx.x & 63) == 0) { sm[w] = m; ss[w] = sum; si[w] = bi; sn[w] = any_nan; }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        tok[c] = bi;
-        conf[c] = 1.0f / se;
+        int n = sn[0];
+        for (int i = 1; i < 4; ++i) {
+            head_merge(m, sum, bi, sm[i], ss[i], si[i]);
+            n |= sn[i];
+        }
+        part[(size_t)c * HEAD_SLICES + slice] = HeadPartial{m, sum, bi, n};
     }
+}
+
+__global__ __launch_bounds__(64) void head_stats_final_kernel(const HeadPartial *__restrict__ part,
+                                                              const int *__restrict__ counts,
+                                                              int *__restrict__ tok, float *__restrict__ conf,
+                                                              int *__restrict__ status) {
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    if (c >= counts[1]) return;
+    float m = -INFINITY, sum = 0.f;
+    int bi = 0x7fffffff, nan = 0;
+    for (int s = 0; s < HEAD_SLICES; ++s) {             // ascending ranges: ties go to the lower token id
+        const HeadPartial p = part[(size_t)c * HEAD_SLICES + s];
+        head_merge(m, sum, bi, p.max, p.sum, p.idx);
+        nan |= p.nan;
+    }
+    if (nan) atomicOr(status, STATUS_NAN);
+    tok[c] = bi;
+    conf[c] = 1.0f / sum;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -543,10 +591,16 @@ int dkv_launch_reduce_partials(hipStream_t s, const float *part, int splits, siz
     return DKV_OK;
 }
 
+size_t dkv_head_stats_scratch_bytes(int cands) { return (size_t)cands * HEAD_SLICES * sizeof(HeadPartial); }
+
 int dkv_launch_head_stats(hipStream_t s, int cands, const float *logits, const int *counts, int V,
-                          int mask_id, int *tok, float *conf, int *status) {
+                          int mask_id, int *tok, float *conf, int *status, void *scratch) {
     if (cands <= 0) return DKV_OK;
-    hipLaunchKernelGGL(head_stats_kernel, dim3(cands), dim3(1024), 0, s, logits, counts, V, mask_id, tok, conf,
+    HeadPartial *part = static_cast<HeadPartial *>(scratch);
+    hipLaunchKernelGGL(head_stats_partial_kernel, dim3(HEAD_SLICES, cands), dim3(256), 0, s, logits, counts, V,
+                       mask_id, part);
+    DKV_LAUNCH_CHECK();
+    hipLaunchKernelGGL(head_stats_final_kernel, dim3((cands + 63) / 64), dim3(64), 0, s, part, counts, tok, conf,
                        status);
     DKV_LAUNCH_CHECK();
     return DKV_OK;
