@@ -23,7 +23,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # paper_2505_15781_amd/kernel_bench.py at the configs[2] layer shapes (FETCH x2.00, WRITE x1.00 after
 # calibration against a 1 GiB copy kernel); see profiles/projection_cfg2_hbm_traffic_pmc.txt.
 # The counters cannot be read inside this program, so `traffic` scales this run's algorithmic bytes.
-MEASURED_TRAFFIC_RATIO = {"gemm_dma<2,2,2,2,3>": 1.54}
+MEASURED_TRAFFIC_RATIO = {"gemm_dma<1,1,1,4,4>": 1.03, "gemm_dma<2,1,1,4,4>": 1.09, "gemm_dma<1,3,4,1,4>": 1.12,
+                          "gemm_dma<2,3,2,2,3>": 1.12, "gemm_dma<2,2,2,2,3>": 1.33, "gemm_dma<2,4,2,2,3>": 1.44,
+                          "gemm_dma<4,4,2,2,2>": 1.12}
 
 
 def parse():
