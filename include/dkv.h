@@ -185,10 +185,11 @@ int dkv_destroy(dkv_ctx *ctx);
 #define DKV_GEMM_DMA_256x256  4
 #define DKV_GEMM_DMA_128x96   5
 #define DKV_GEMM_DMA_128x192  6
-#define DKV_GEMM_REG_64x128   7   /* bf16 with K not a multiple of 64 */
-#define DKV_GEMM_SIMT         8   /* fp32 mode / generic */
-#define DKV_PROF_ATTN         9   /* attention (including the key-slice merge when it runs) */
-#define DKV_PROF_KINDS        10
+#define DKV_GEMM_DMA_256x192  7
+#define DKV_GEMM_REG_64x128   8   /* bf16 with K not a multiple of 64 */
+#define DKV_GEMM_SIMT         9   /* fp32 mode / generic */
+#define DKV_PROF_ATTN         10  /* attention (including the key-slice merge when it runs) */
+#define DKV_PROF_KINDS        11
 typedef struct {
     int64_t launches;
     double ms, bytes, flops;

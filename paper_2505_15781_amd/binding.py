@@ -61,10 +61,11 @@ class ProfEntry(C.Structure):
 
 
 PROF_KINDS = ("gemm_dma<1,1,1,4,4>", "gemm_dma<2,1,1,4,4>", "gemm_dma<2,2,2,2,3>", "gemm_dma<2,4,2,2,3>",
-              "gemm_dma<4,4,2,2,2>", "gemm_dma<1,3,4,1,4>", "gemm_dma<2,3,2,2,3>", "gemm_reg", "gemm_simt",
+              "gemm_dma<4,4,2,2,2>", "gemm_dma<1,3,4,1,4>", "gemm_dma<2,3,2,2,3>", "gemm_dma<4,3,2,2,2>", "gemm_reg",
+              "gemm_simt",
               "attention")
 GEMM_KINDS = {"dma_32x128": 0, "dma_64x128": 1, "dma_128x128": 2, "dma_128x256": 3, "dma_256x256": 4,
-              "dma_128x96": 5, "dma_128x192": 6, "reg_64x128": 7, "simt": 8}
+              "dma_128x96": 5, "dma_128x192": 6, "dma_256x192": 7, "reg_64x128": 8, "simt": 9}
 lib.dkv_profile_begin.argtypes = [c_vp]
 lib.dkv_profile_end.argtypes = [c_vp, C.POINTER(ProfEntry)]
 lib.dkv_attn_update_workspace_bytes.restype = c_sz

@@ -329,8 +329,9 @@ constexpr KindInfo kKinds[] = {
     {256, 256},   // GEMM_DMA_256x256  <4,4,2,2> 2 stages
     {128, 96},    // GEMM_DMA_128x96   <1,3,4,1> 4 stages
     {128, 192},   // GEMM_DMA_128x192  <2,3,2,2> 3 stages
+    {256, 192},   // GEMM_DMA_256x192  <4,3,2,2> 2 stages
 };
-static_assert(sizeof(kKinds) / sizeof(kKinds[0]) == GEMM_DMA_128x192 + 1, "one entry per gemm_dma kind");
+static_assert(sizeof(kKinds) / sizeof(kKinds[0]) == GEMM_DMA_256x192 + 1, "one entry per gemm_dma kind");
 
 
 template <int MT, int NT, int WM, int WN, int STAGES>
@@ -388,7 +389,8 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     //   no launch beats streaming its operands and results once;
     //   K slices add the write and re-read of their partial sums by the consumer.
     // Tiles of 96 and 192 columns exist because 12288 / 96 = 128 and 24576 / 192 = 128 column tiles make
-    // exactly one or two full rounds where 128- and 256-column tiles leave a quarter of the chip idle.
+    // exactly one or two full rounds where 128- and 256-column tiles leave a quarter of the chip idle
+    // (256x192 does the same for 257..512 rows of the widest projection).
     constexpr double kFillPerCu = 48785.0, kFlopsPerCu = 5332277.0, kFillAll = 14076233.0;   // bytes, flops per us
     constexpr double kStream = 7841520.0, kReduce = 1819886.0;                                  // bytes per us
     constexpr double kLaunch = 3.5, kPipeFill = 0.7, kReduceFixed = 1.7;                        // us
@@ -396,7 +398,7 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     const int kt_total = k / BK;
     double best = 0.0;
     p.kind = -1;
-    for (int kind = 0; kind <= GEMM_DMA_128x192; ++kind) {
+    for (int kind = 0; kind <= GEMM_DMA_256x192; ++kind) {
         const KindInfo &ki = kKinds[kind];
         if (ki.bm > 32 && ki.bm >= 4 * m_upper) continue;       // mostly padding
         if (ki.bm < 128 && m_upper > 4 * ki.bm) continue;       // W re-read too often
@@ -425,10 +427,11 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     }
     // Launch options, from the same sweep: a staggered K start pays when one row of tiles sweeps K unsplit or
     // in two slices (all workgroups would otherwise read the same A columns at once); the XCD-grouped order
-    // pays for the two largest tiles once there are enough tile rows to form 4-row groups.
+    // pays for the largest tiles once there are enough tile rows to form 4-row groups.
     const int tiles_m = ceil_div(m_upper, kKinds[p.kind].bm);
     if (tiles_m == 1 && p.split_k <= 2) p.flags |= GEMM_FLAG_STAGGER;
-    if ((p.kind == GEMM_DMA_256x256 && tiles_m >= 4) || (p.kind == GEMM_DMA_128x256 && tiles_m >= 6))
+    if (((p.kind == GEMM_DMA_256x256 || p.kind == GEMM_DMA_256x192) && tiles_m >= 4) ||
+        (p.kind == GEMM_DMA_128x256 && tiles_m >= 6))
         p.flags |= GEMM_FLAG_XCD_GROUP;
     // Giving 256 workgroups 3/4 of a tile's K range each (frac_units, kept for experiments through
     // dkv_gemm_with) was measured to take the same time as two full slices, so it is never planned.
@@ -439,7 +442,7 @@ int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p) {
     if (p.split_k < 1 || p.kind < 0 || p.kind >= GEMM_KINDS || p.frac_units < 0) return 0;
     if (p.frac_units) {
         // a 3/4 share: every tile is covered by exactly two workgroups
-        if (p.kind > GEMM_DMA_128x192 || dtype != DKV_BF16 || (k % BK) != 0) return 0;
+        if (p.kind > GEMM_DMA_256x192 || dtype != DKV_BF16 || (k % BK) != 0) return 0;
         return p.split_k == 2 && (k / BK) % 4 == 0 && p.frac_units == (k / BK) * 3 / 4;
     }
     if (p.kind == GEMM_SIMT) return p.split_k == 1;
@@ -470,6 +473,8 @@ int dkv_launch_gemm(int dtype, const void *A, const void *W, float *partial, int
             return launch_dma<1, 3, 4, 1, 4>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
         case GEMM_DMA_128x192:
             return launch_dma<2, 3, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
+        case GEMM_DMA_256x192:
+            return launch_dma<4, 3, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, stream);
         case GEMM_REG_64x128: {
             const int kt_total = ceil_div(k, BK), kps = ceil_div(kt_total, p.split_k);
             dim3 grid(ceil_div(n, 128), ceil_div(m_upper, 64), p.split_k);

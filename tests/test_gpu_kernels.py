@@ -32,7 +32,8 @@ def test_projection_matches_float64_product(dtype, m, n, k):
 @pytest.mark.parametrize("kind,split", [("dma_32x128", 1), ("dma_32x128", 3), ("dma_64x128", 2), ("dma_128x128", 1),
                                         ("dma_128x128", 4), ("dma_128x256", 2), ("dma_256x256", 1),
                                         ("dma_256x256", 3), ("dma_128x96", 1), ("dma_128x96", 2),
-                                        ("dma_128x192", 1), ("dma_128x192", 3), ("reg_64x128", 2)])
+                                        ("dma_128x192", 1), ("dma_128x192", 3), ("dma_256x192", 1), ("dma_256x192", 2),
+                                        ("reg_64x128", 2)])
 @pytest.mark.parametrize("m,n,k", [(1, 128, 64), (37, 200, 192), (129, 384, 1024), (300, 520, 640), (513, 256, 2048)])
 def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
     import paper_2505_15781_amd as P
@@ -50,7 +51,7 @@ def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
 
 
 @pytest.mark.parametrize("kind", ["dma_32x128", "dma_64x128", "dma_128x128", "dma_128x256", "dma_256x256",
-                                  "dma_128x96", "dma_128x192"])
+                                  "dma_128x96", "dma_128x192", "dma_256x192"])
 @pytest.mark.parametrize("options", [1, 2, 3])
 @pytest.mark.parametrize("m,n,k,split", [(5, 128, 256, 1), (129, 384, 1024, 1), (300, 520, 768, 2),
                                          (1100, 1536, 512, 1), (1030, 2048, 640, 2)])
