@@ -91,9 +91,10 @@ def attn_microbench(torch, P, D):
 
 
 def cpu_baseline(D, model, run, wseed, pseed):
-    """The oracle, as it stands, on a bounded sample: the first 6 denoising steps (512, 257 ... 253 active
-    rows) of the same configuration with the model cut to 4 of its layers; per-layer time is scaled to
-    the full depth, the vocabulary head is timed in full."""
+    """The oracle, as it stands, on a bounded sample: the first 16 denoising steps (two refresh steps with
+    all 512 rows active and 14 cached steps with 257 ... 243 rows: the mix of a refresh interval of 8) of
+    the same configuration with the model cut to 4 of its layers; per-layer time is scaled to the full
+    depth, the vocabulary head is timed in full."""
     from threadpoolctl import threadpool_info
     from oracle import sampler as SA
     from oracle import model as OM
@@ -105,7 +106,7 @@ def cpu_baseline(D, model, run, wseed, pseed):
     for l in range(n_small):
         synth.layer(l)                                                  # generation is not oracle time
     st = SA.init_state(small, run, prompt)
-    n_steps = 6
+    n_steps = min(16, run.steps)
     t_body = t_head = 0.0
     for t in range(n_steps):
         # time body and head separately by running the forward twice would double the cost; instead time
