@@ -47,6 +47,7 @@ class RunShape:
     window_center: int = CENTER_CUR
     include_prev: int = 1
     remask: int = CONFIDENCE
+    shift_logits: int = 0
 
     @property
     def seq_len(self):

@@ -85,10 +85,12 @@ def denoise_step(model, weights, run, st, t, order=None, forced=None, forced_sco
     conf = np.zeros((B, k), dtype=np.float32)
     for b in range(B):
         c = S.candidates(run, t, active[b], st.masked[b])
-        rows = [off[b] + active[b].index(p) for p in c]
+        # the row whose output is the distribution of position p: p itself, or p - 1 under shifted logits
+        src = [active[b].index(p - (1 if run.shift_logits else 0)) for p in c]
+        rows = [off[b] + i for i in src]
         if head_all_rows:
             all_logits = logits_of(model, weights, h[off[b]:off[b + 1]])
-            lg = all_logits[[active[b].index(p) for p in c]]
+            lg = all_logits[src]
         else:
             lg = logits_of(model, weights, h[rows])
         tk, cf = predict(lg, model.mask_id)

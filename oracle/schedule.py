@@ -17,7 +17,8 @@ def validate_run(run):
           and run.block_len >= 1 and run.refresh_interval >= 1
           and run.gen_len % run.block_len == 0
           and run.steps % (run.gen_len // run.block_len) == 0
-          and run.block_len % (run.steps // (run.gen_len // run.block_len)) == 0)
+          and run.block_len % (run.steps // (run.gen_len // run.block_len)) == 0
+          and (not run.shift_logits or run.prompt_len >= 1))
     return ok
 
 
@@ -50,8 +51,8 @@ def refresh_scope_positions(run, scope):
     raise ValueError("unknown refresh scope")
 
 
-def select_active(run, t, masked, d_prev, d_cur=None, forced_scope=None):
-    """Active positions of ONE sequence at step t, sorted ascending, unique.
+def _select_unshifted(run, t, masked, d_prev, d_cur=None, forced_scope=None):
+    """Active positions of ONE sequence at step t without the extra rows of shifted logits.
 
     masked : sequence of L booleans, the mask set in the INPUT of step t (M_t).
     d_prev : positions committed at step t-1 (D_{t-1}; empty at t = 0).
@@ -96,6 +97,22 @@ def select_active(run, t, masked, d_prev, d_cur=None, forced_scope=None):
                 act |= set(window(c, run.window, L))
         return sorted(p for p in act if 0 <= p < L)
     raise ValueError("unknown variant")
+
+
+def select_active(run, t, masked, d_prev, d_cur=None, forced_scope=None):
+    """Active positions of ONE sequence at step t, sorted ascending, unique (see _select_unshifted
+    for the sets of each variant).
+
+    With run.shift_logits (a model adapted from an autoregressive one, Appendix B: the output at
+    position i is the distribution of token i + 1, and K/V are cached unshifted, at the token's own
+    position) the row that predicts a candidate q is q - 1, so q - 1 joins the active set for every
+    position q that may be committed at this step."""
+    act = _select_unshifted(run, t, masked, d_prev, d_cur, forced_scope)
+    if run.shift_logits:
+        extra = {q - 1 for q in candidates(run, t, act, masked)}
+        assert all(p >= 0 for p in extra)
+        act = sorted(set(act) | extra)
+    return act
 
 
 def candidates(run, t, active, masked):

@@ -167,6 +167,45 @@ def test_one_layer_model_with_one_step_delay_reproduces_full_recomputation(N):
     assert max(diffs) > 1e-6
 
 
+@pytest.mark.parametrize("N,variant", [(1, DECODE), (3, DECODE), (100, DECODE), (2, PD), (2, PREFILL)])
+def test_shifted_logits_read_the_previous_row_and_stay_exact_with_one_layer(N, variant):
+    # Appendix B (Un-Shift): the prediction for position q is the output of row q - 1. Checked against a
+    # cache-free forward over all positions read at q - 1; with one layer the cached run must agree exactly
+    # for any refresh interval, and it must differ from reading the logits at q itself.
+    model = ModelShape(**{**SMALL.__dict__, "n_layers": 1})
+    run = RunShape(batch=2, prompt_len=5, gen_len=8, steps=8, block_len=4, refresh_interval=N, variant=variant,
+                   shift_logits=1)
+    w, prompt = _weights(model), _prompt(model, run)
+    st = SA.init_state(model, run, prompt)
+    differs = False
+    for t in range(run.steps):
+        tokens_in = st.tokens.copy()
+        log = SA.denoise_step(model, w, run, st, t, keep_logits=True)
+        h_full, _ = M.full_forward(model, w, tokens_in)
+        lg_full = M.logits_of(model, w, h_full).reshape(run.batch, run.seq_len, -1)
+        for b in range(run.batch):
+            assert all(q - 1 in log.active[b] for q in log.cand[b])
+            for q, lg in _logits_by_pos(log, b).items():
+                assert np.allclose(lg, lg_full[b, q - 1], rtol=1e-11, atol=1e-13)
+                differs |= np.max(np.abs(lg - lg_full[b, q])) > 1e-6
+    assert differs
+
+
+def test_shifted_logits_with_refresh_every_step_equal_cache_free_recomputation_at_depth():
+    model = SMALL
+    run = RunShape(batch=2, prompt_len=5, gen_len=8, steps=8, block_len=4, refresh_interval=1, shift_logits=1)
+    w, prompt = _weights(model), _prompt(model, run)
+    st = SA.init_state(model, run, prompt)
+    for t in range(run.steps):
+        tokens_in = st.tokens.copy()
+        log = SA.denoise_step(model, w, run, st, t, keep_logits=True)
+        h_full, _ = M.full_forward(model, w, tokens_in)
+        lg_full = M.logits_of(model, w, h_full).reshape(run.batch, run.seq_len, -1)
+        for b in range(run.batch):
+            for q, lg in _logits_by_pos(log, b).items():
+                assert np.allclose(lg, lg_full[b, q - 1], rtol=1e-13, atol=1e-15)
+
+
 @pytest.mark.parametrize("include_prev", [1, 0])
 def test_one_layer_greedy_is_exact_only_when_the_previous_commit_is_recomputed(include_prev):
     model = ModelShape(**{**SMALL.__dict__, "n_layers": 1})

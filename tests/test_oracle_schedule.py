@@ -86,6 +86,30 @@ def test_decode_active_set_is_masked_plus_previous_commit():
     assert S.select_active(run, 2, masked, [4], forced_scope=SCOPE_ALL) == list(range(8))
 
 
+def test_shifted_logits_add_the_row_before_every_candidate():
+    # Appendix B: a model adapted from an autoregressive one predicts token q at row q - 1, so that row is
+    # recomputed whenever q may be committed; nothing else changes.
+    masked = [False, False, False, True, False, True, True, False]
+    run = RunShape(batch=1, prompt_len=3, gen_len=5, steps=5, block_len=5, refresh_interval=100, shift_logits=1)
+    # masked 3, 5, 6 (+ previous commit 4): candidates 3, 5, 6 need rows 2, 4, 5 -> 2 joins
+    assert S.select_active(run, 2, masked, [4]) == [2, 3, 4, 5, 6]
+    nodelay = RunShape(batch=1, prompt_len=3, gen_len=5, steps=5, block_len=5, refresh_interval=100, delay=0,
+                       shift_logits=1)
+    assert S.select_active(nodelay, 2, masked, [4]) == [2, 3, 4, 5, 6]          # 4 returns as the row before 5
+    # two blocks of 4: only candidates of the current block pull their predecessor in
+    m2 = [False, False, True, False, True, True, True, True, True, True]
+    blocks = RunShape(batch=1, prompt_len=2, gen_len=8, steps=8, block_len=4, refresh_interval=100, shift_logits=1)
+    assert S.select_active(blocks, 1, m2, []) == [1, 2, 3, 4, 5, 6, 7, 8, 9]     # candidates 2, 4, 5: rows 1, 3
+    plain = RunShape(batch=1, prompt_len=2, gen_len=8, steps=8, block_len=4, refresh_interval=100)
+    assert S.select_active(plain, 1, m2, []) == [2, 4, 5, 6, 7, 8, 9]
+    # generated-region-only sets (Prefill, PD refresh) reach one row into the prompt
+    pre = RunShape(batch=1, prompt_len=3, gen_len=5, steps=5, block_len=5, refresh_interval=2, variant=PREFILL,
+                   shift_logits=1)
+    assert S.select_active(pre, 1, masked, [4]) == [2, 3, 4, 5, 6, 7]
+    assert not S.validate_run(RunShape(batch=1, prompt_len=0, gen_len=4, steps=4, block_len=4, refresh_interval=2,
+                                       shift_logits=1))
+
+
 def test_prefill_and_pd_active_sets():
     masked = [False, False, False, True, False, True, True, False]
     pre = RunShape(batch=1, prompt_len=3, gen_len=5, steps=5, block_len=5, refresh_interval=2, variant=PREFILL)
