@@ -100,6 +100,11 @@ typedef struct {
     int32_t window, window_center, include_prev;   /* Greedy: window size w, its centre, and whether
                                                       the previous step's commits are recomputed */
     int32_t remask;                    /* DKV_CONFIDENCE | DKV_RANDOM_ORDER */
+    int32_t shift_logits;              /* 0: the output at position q is the distribution of token q;
+                                          1: of token q + 1 (models adapted from autoregressive ones,
+                                          Appendix B, K/V cached unshifted): the row before every
+                                          position that may be committed joins the active set and
+                                          supplies its logits. Needs prompt_len >= 1. */
     const int32_t *order;              /* (dev) [batch, gen_len] absolute positions in commit order;
                                           DKV_RANDOM_ORDER only (required by DKV_GREEDY) */
 } dkv_run_desc;

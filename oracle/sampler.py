@@ -84,7 +84,7 @@ def denoise_step(model, weights, run, st, t, order=None, forced=None, forced_sco
     tok = np.zeros((B, k), dtype=np.int32)
     conf = np.zeros((B, k), dtype=np.float32)
     for b in range(B):
-        c = S.candidates(run, t, active[b], st.masked[b])
+        c = S.step_candidates(run, t, st.masked[b], st.d_prev[b], d_cur[b], forced_scope)
         # the row whose output is the distribution of position p: p itself, or p - 1 under shifted logits
         src = [active[b].index(p - (1 if run.shift_logits else 0)) for p in c]
         rows = [off[b] + i for i in src]

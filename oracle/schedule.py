@@ -115,6 +115,12 @@ def select_active(run, t, masked, d_prev, d_cur=None, forced_scope=None):
     return act
 
 
+def step_candidates(run, t, masked, d_prev, d_cur=None, forced_scope=None):
+    """Positions whose prediction may be committed at step t: members of the variant's own set (the
+    rows added for shifted logits do not count) that are still masked and lie in the block."""
+    return candidates(run, t, _select_unshifted(run, t, masked, d_prev, d_cur, forced_scope), masked)
+
+
 def candidates(run, t, active, masked):
     """Rows whose prediction may be committed at step t: active, still masked, in the block."""
     lo, hi = block_range(run, t)

@@ -33,7 +33,8 @@ class Weights(C.Structure):
 
 class RunDesc(C.Structure):
     _fields_ = [(n, c_i32) for n in ("batch", "prompt_len", "gen_len", "steps", "block_len", "refresh_interval",
-                                     "variant", "delay", "window", "window_center", "include_prev", "remask")] + \
+                                     "variant", "delay", "window", "window_center", "include_prev", "remask",
+                                     "shift_logits")] + \
                [("order", c_vp)]
 
 
@@ -111,7 +112,7 @@ def model_desc(m):
 
 def run_desc(r, order_ptr=None):
     return RunDesc(r.batch, r.prompt_len, r.gen_len, r.steps, r.block_len, r.refresh_interval, r.variant, r.delay,
-                   r.window, r.window_center, r.include_prev, r.remask, order_ptr)
+                   r.window, r.window_center, r.include_prev, r.remask, getattr(r, "shift_logits", 0), order_ptr)
 
 
 def upload_weights(model, synth, device="cuda", layers=None):

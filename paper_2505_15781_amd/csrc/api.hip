@@ -35,6 +35,7 @@ bool run_ok(const dkv_run_desc &r) {
     if (r.remask != DKV_CONFIDENCE && r.remask != DKV_RANDOM_ORDER) return false;
     if (r.variant == DKV_GREEDY && r.remask != DKV_RANDOM_ORDER) return false;
     if (r.window < 0 || (r.delay != 0 && r.delay != 1)) return false;
+    if (r.shift_logits != 0 && (r.shift_logits != 1 || r.prompt_len < 1)) return false;
     return true;
 }
 
@@ -214,9 +215,12 @@ void step_bounds(const dkv_ctx *c, int t, int scope, int *mode, int *rows_per_se
         rows = G - t * k + (r.delay ? k : 0);
     }
     const int in_block = r.block_len - (t % c->spb) * k;
+    const int cands = in_block < rows ? in_block : rows;
+    // shifted logits: every candidate may pull the row before it into the set
+    if (r.shift_logits && md != SEL_ALL) rows = rows + cands < L ? rows + cands : L;
     *mode = md;
     *rows_per_seq = rows;
-    *cand_per_seq = in_block < rows ? in_block : rows;
+    *cand_per_seq = cands;
 }
 
 int do_select(dkv_ctx *c, int step) {
@@ -240,6 +244,7 @@ int do_select(dkv_ctx *c, int step) {
     const int j = step / c->spb;
     a.blk_lo = r.prompt_len + j * r.block_len;
     a.blk_hi = a.blk_lo + r.block_len;
+    a.shift = r.shift_logits;
     int rc = dkv_launch_select(a, c->stream);
     if (rc) return rc;
     c->rows_per_seq_upper = rps;

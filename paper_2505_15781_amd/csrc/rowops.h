@@ -17,6 +17,7 @@ struct SelectArgs {
     int batch, L, P, G, k, step;
     int mode, use_prev, center_prev, window, win_lo, win_hi;
     int blk_lo, blk_hi;
+    int shift;               // 1: a candidate's prediction is the output of the row before it
 };
 
 struct CommitArgs {

@@ -45,24 +45,32 @@ __global__ __launch_bounds__(1024) void select_active_kernel(SelectArgs a) {
             const int p = p0 + threadIdx.x;
             int act = 0, cand = 0;
             if (p < a.L) {
-                const bool m = mk[p] != 0;
-                if (a.mode == SEL_ALL) act = 1;
-                else if (a.mode == SEL_GEN) act = p >= a.P;
-                else if (a.mode == SEL_MASKED_PREV) {
-                    act = m;
-                    if (!act && a.use_prev)
-                        for (int j = 0; j < a.k; ++j) act |= (a.d_prev[b * a.k + j] == p);
-                } else {   // SEL_GREEDY
+                // membership of position x in the variant's set, and whether x may be committed at this step
+                auto in_set = [&](int x) -> bool {
+                    if (a.mode == SEL_ALL) return true;
+                    if (a.mode == SEL_GEN) return x >= a.P;
+                    if (a.mode == SEL_MASKED_PREV) {
+                        bool f = mk[x] != 0;
+                        if (!f && a.use_prev)
+                            for (int j = 0; j < a.k; ++j) f |= (a.d_prev[b * a.k + j] == x);
+                        return f;
+                    }
+                    bool f = false;   // SEL_GREEDY
                     for (int j = 0; j < a.k; ++j) {
                         const int cur = a.order[(size_t)b * a.G + a.step * a.k + j];
                         const int prev = a.d_prev[b * a.k + j];
-                        act |= (cur == p);
-                        if (a.use_prev) act |= (prev == p);
+                        f |= (cur == x);
+                        if (a.use_prev) f |= (prev == x);
                         const int c = a.center_prev ? prev : cur;
-                        if (a.window > 0 && c >= 0) act |= (p >= c - a.win_lo && p <= c + a.win_hi);
+                        if (a.window > 0 && c >= 0) f |= (x >= c - a.win_lo && x <= c + a.win_hi);
                     }
-                }
-                cand = act && m && p >= a.blk_lo && p < a.blk_hi;
+                    return f;
+                };
+                auto is_cand = [&](int x) -> bool { return x >= a.blk_lo && x < a.blk_hi && mk[x] != 0 && in_set(x); };
+                cand = is_cand(p);
+                act = in_set(p);
+                // shifted logits (Appendix B): the row before a candidate produces its prediction
+                if (a.shift && !act && p + 1 < a.L) act = is_cand(p + 1);
             }
             int tot_a, tot_c;
             const int ia = block_excl_scan(act, wave_tot, &tot_a);
@@ -72,7 +80,8 @@ __global__ __launch_bounds__(1024) void select_active_kernel(SelectArgs a) {
                 a.row_seq[row_base + ia] = b;
             }
             if (cand) {
-                a.cand_row[cand_base + ic] = row_base + ia;
+                // with shifted logits position p - 1 is active and precedes p directly in the row order
+                a.cand_row[cand_base + ic] = row_base + ia - (a.shift ? 1 : 0);
                 a.cand_pos[cand_base + ic] = p;
             }
             row_base += tot_a;

@@ -44,6 +44,25 @@ def test_greedy_variant_with_window(center, include_prev):
     run_side_by_side(SMALL_BF16, run, 11, 12, order_seed=13)
 
 
+@pytest.mark.parametrize("variant", [DECODE, PD, PREFILL, GREEDY])
+def test_shifted_logits_use_the_row_before_each_candidate(variant):
+    """Appendix B (Un-Shift): row q - 1 predicts position q and joins the active set; several blocks so that
+    the extra rows appear in the middle of the generated region, batch 3 so that they appear at sequence starts
+    of the row list."""
+    kw = dict(remask=RANDOM_ORDER, window=2) if variant == GREEDY else {}
+    run = RunShape(batch=3, prompt_len=11, gen_len=24, steps=24, block_len=8, refresh_interval=5, variant=variant,
+                   shift_logits=1, **kw)
+    run_side_by_side(SMALL_FP32, run, 21, 22, order_seed=23 if variant == GREEDY else None)
+    run_side_by_side(SMALL_BF16, run, 21, 22, order_seed=23 if variant == GREEDY else None)
+
+
+def test_shifted_logits_free_running_fp32_reproduces_the_oracle_tokens():
+    run = RunShape(batch=2, prompt_len=9, gen_len=16, steps=16, block_len=8, refresh_interval=4, shift_logits=1)
+    g, st, _ = run_side_by_side(SMALL_FP32, run, 24, 25, teacher_forced=False)
+    assert np.array_equal(g.decoded_pos.cpu().numpy(), np.stack([l.pos for l in st.logs]))
+    assert np.array_equal(g.decoded_tok.cpu().numpy(), np.stack([l.tok for l in st.logs]))
+
+
 def test_explicit_refresh_out_of_schedule():
     run = RunShape(batch=2, prompt_len=7, gen_len=16, steps=16, block_len=16, refresh_interval=100)
     run_side_by_side(SMALL_FP32, run, 14, 15, forced_scopes={3: SCOPE_ALL, 9: SCOPE_GEN})

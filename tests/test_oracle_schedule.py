@@ -108,6 +108,12 @@ def test_shifted_logits_add_the_row_before_every_candidate():
     assert S.select_active(pre, 1, masked, [4]) == [2, 3, 4, 5, 6, 7]
     assert not S.validate_run(RunShape(batch=1, prompt_len=0, gen_len=4, steps=4, block_len=4, refresh_interval=2,
                                        shift_logits=1))
+    # Greedy: the added row may itself be masked and in the block, but it is not a candidate of the step
+    gr = RunShape(batch=1, prompt_len=2, gen_len=8, steps=8, block_len=8, refresh_interval=100, variant=GREEDY,
+                  window=0, remask=RANDOM_ORDER, shift_logits=1)
+    m3 = [False, False, True, True, True, True, True, True, True, True]
+    assert S.select_active(gr, 1, m3, [], d_cur=[6]) == [5, 6]
+    assert S.step_candidates(gr, 1, m3, [], d_cur=[6]) == [6]
 
 
 def test_prefill_and_pd_active_sets():
