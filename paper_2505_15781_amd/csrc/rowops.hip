@@ -99,8 +99,8 @@ __global__ __launch_bounds__(1024) void select_active_kernel(SelectArgs a) {
 // ------------------------------------------------------------------------------------------------
 // h[r] = embed[token at (seq, pos)], a[r] = RMSNorm(h[r]) * gain; stamps the row's position.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int VPT>
-__global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ embed,
+template <typename T, int VPT, int NT>
+__global__ __launch_bounds__(NT) void embed_norm_kernel(const T *__restrict__ embed,
                                                          const int *__restrict__ tokens,
                                                          const int *__restrict__ row_pos,
                                                          const int *__restrict__ row_seq,
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ e
     float v[VPT], ss = 0.f;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
-        int c = threadIdx.x + 256 * i;
+        int c = threadIdx.x + NT * i;
         v[i] = c < d ? El<T>::ld(e + c) : 0.f;
         ss += v[i] * v[i];
     }
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ e
     const float rs = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
-        int c = threadIdx.x + 256 * i;
+        int c = threadIdx.x + NT * i;
         if (c < d) {
             h[(size_t)r * d + c] = v[i];
             El<T>::st(a + (size_t)r * d + c, v[i] * rs * gain[c]);
@@ -147,9 +147,9 @@ __device__ __forceinline__ void store4(bf16_t *p, float4 v) {
 }
 __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
-// one workgroup per row, float4 per lane: d must be a multiple of 4 and at most 1024 * V4
-template <typename T, int V4>
-__global__ __launch_bounds__(256) void residual_norm_kernel(const float *__restrict__ part, int splits,
+// one workgroup of NT threads per row, V4 float4 per lane: d must be a multiple of 4 and at most 4 * NT * V4
+template <typename T, int V4, int NT>
+__global__ __launch_bounds__(NT) void residual_norm_kernel(const float *__restrict__ part, int splits,
                                                             size_t split_stride,
                                                             const int *__restrict__ counts,
                                                             const float *__restrict__ gain,
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(const float *__restr
     float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
-        const int c = (threadIdx.x + 256 * i) * 4;
+        const int c = (threadIdx.x + NT * i) * 4;
         float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
         if (c < d) {
             const size_t at = (size_t)r * d + c;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(const float *__restr
     const float rs = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
-        const int c = (threadIdx.x + 256 * i) * 4;
+        const int c = (threadIdx.x + NT * i) * 4;
         if (c < d) {
             const size_t at = (size_t)r * d + c;
             *reinterpret_cast<float4 *>(h + at) = v[i];
@@ -207,7 +207,8 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float *__restri
     const int b = row_seq[r], p = row_pos[r];
     const int half = dh >> 1, q4 = half >> 2, slots = Hq + 2 * Hkv, n = slots * dh;
     const float *src = part + (size_t)r * n;
-    for (int e = threadIdx.x; e < slots * q4; e += 256) {
+    // grid.y workgroups share a row: many small workgroups hide the load latency better than one long loop
+    for (int e = blockIdx.y * 256 + threadIdx.x; e < slots * q4; e += 256 * gridDim.y) {
         const int hs = e / q4, i = (e % q4) * 4;
         float4 x1 = make_float4(0.f, 0.f, 0.f, 0.f), x2 = x1;
 #pragma unroll 4
@@ -487,13 +488,13 @@ template <typename T> int vpt_dispatch_embed(hipStream_t s, int rows, int d, con
                                              const int *row_pos, const int *row_seq, const int *counts,
                                              const float *gain, float *h, T *a, int *stamp, int L, float eps,
                                              int step) {
-#define GO(V)                                                                                              \
-    hipLaunchKernelGGL((embed_norm_kernel<T, V>), dim3(rows), dim3(256), 0, s, embed, tokens, row_pos,     \
+#define GO(V, NT)                                                                                          \
+    hipLaunchKernelGGL((embed_norm_kernel<T, V, NT>), dim3(rows), dim3(NT), 0, s, embed, tokens, row_pos,  \
                        row_seq, counts, gain, h, a, stamp, L, d, eps, step)
-    if (d <= 256) GO(1);
-    else if (d <= 1024) GO(4);
-    else if (d <= 4096) GO(16);
-    else if (d <= 8192) GO(32);
+    if (d <= 256) GO(1, 256);
+    else if (d <= 1024) GO(1, 1024);
+    else if (d <= 4096) GO(4, 1024);
+    else if (d <= 8192) GO(8, 1024);
     else { dkv_set_error("d_model %d above 8192 is not supported", d); return DKV_E_UNSUPPORTED; }
 #undef GO
     DKV_LAUNCH_CHECK();
@@ -503,14 +504,15 @@ template <typename T> int vpt_dispatch_embed(hipStream_t s, int rows, int d, con
 template <typename T> int vpt_dispatch_resnorm(hipStream_t s, int rows, int d, const float *part, int splits,
                                                size_t stride, const int *counts, const float *gain, float *h,
                                                T *a, float eps) {
-#define GO(V)                                                                                              \
-    hipLaunchKernelGGL((residual_norm_kernel<T, V>), dim3(rows), dim3(256), 0, s, part, splits, stride,    \
+#define GO(V, NT)                                                                                          \
+    hipLaunchKernelGGL((residual_norm_kernel<T, V, NT>), dim3(rows), dim3(NT), 0, s, part, splits, stride, \
                        counts, gain, h, a, d, eps)
     if (d % 4) { dkv_set_error("d_model %d must be a multiple of 4", d); return DKV_E_UNSUPPORTED; }
-    if (d <= 1024) GO(1);
-    else if (d <= 2048) GO(2);
-    else if (d <= 4096) GO(4);
-    else if (d <= 8192) GO(8);
+    // one float4 per lane per slice where the row is long enough: more wavefronts per row hide the load latency
+    if (d <= 1024) GO(1, 256);
+    else if (d <= 2048) GO(1, 512);
+    else if (d <= 4096) GO(1, 1024);
+    else if (d <= 8192) GO(2, 1024);
     else { dkv_set_error("d_model %d above 8192 is not supported", d); return DKV_E_UNSUPPORTED; }
 #undef GO
     DKV_LAUNCH_CHECK();
@@ -552,12 +554,16 @@ int dkv_launch_rope_scatter(int dtype, hipStream_t s, int rows, const float *par
                             const int *row_pos, const int *row_seq, const int *counts, const float *rope,
                             void *q, void *Kc, void *Vc, int Hq, int Hkv, int dh, int L) {
     if (rows <= 0) return DKV_OK;
+    const int per_row = (Hq + 2 * Hkv) * (dh / 8);          // float4 pairs of a row
+    int gy = ceil_div(per_row, 256);
+    if (gy > 8) gy = 8;
+    const dim3 grid(rows, gy);
     if (dtype == DKV_BF16)
-        hipLaunchKernelGGL((rope_scatter_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, part, splits, stride,
+        hipLaunchKernelGGL((rope_scatter_kernel<bf16_t>), grid, dim3(256), 0, s, part, splits, stride,
                            row_pos, row_seq, counts, (const float2 *)rope, (bf16_t *)q, (bf16_t *)Kc,
                            (bf16_t *)Vc, Hq, Hkv, dh, L);
     else
-        hipLaunchKernelGGL((rope_scatter_kernel<float>), dim3(rows), dim3(256), 0, s, part, splits, stride,
+        hipLaunchKernelGGL((rope_scatter_kernel<float>), grid, dim3(256), 0, s, part, splits, stride,
                            row_pos, row_seq, counts, (const float2 *)rope, (float *)q, (float *)Kc,
                            (float *)Vc, Hq, Hkv, dh, L);
     DKV_LAUNCH_CHECK();
