@@ -224,6 +224,19 @@ int dkv_attn_update(void *k_cache, void *v_cache, const void *q, const void *k_n
                     int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim,
                     int32_t dtype, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The paper's own cache operator, concat_reorder (Appendix A; Algorithm 1 lines 4-5), on its compact
+ * layout: per (sequence, kv head) the n_cached cached rows and the n_new freshly computed rows are
+ * concatenated and row i of the result is row take[b][i] of that concatenation (the order that puts the next
+ * step's cached positions first). Not on this library's path (the position-indexed cache never moves);
+ * exported so that what the layout choice saves can be measured on the same shapes.
+ * All (dev): k_cached, v_cached [batch][n_kv_heads][n_cached][head_dim]; k_new, v_new [batch][n_kv_heads]
+ * [n_new][head_dim]; take [batch][n_cached + n_new], a permutation of 0 .. n_cached + n_new - 1 per
+ * sequence (values are not checked); k_out, v_out [batch][n_kv_heads][n_cached + n_new][head_dim], must not
+ * overlap the inputs. head_dim * element size must be a multiple of 16. */
+int dkv_concat_reorder(const void *k_cached, const void *v_cached, const void *k_new, const void *v_new,
+                       const int32_t *take, void *k_out, void *v_out, int32_t batch, int32_t n_kv_heads,
+                       int32_t n_cached, int32_t n_new, int32_t head_dim, int32_t dtype, void *stream);
+
 /* y[M, N] (fp32, dev) = x[M, K] * w[N, K]^T with x, w of `dtype` (dev): the projection kernel of
  * the path on its own, for parity tests and roofline measurements. workspace as returned by
  * dkv_gemm_workspace_bytes. */

@@ -72,6 +72,7 @@ lib.dkv_profile_end.argtypes = [c_vp, C.POINTER(ProfEntry)]
 lib.dkv_attn_update_workspace_bytes.restype = c_sz
 lib.dkv_attn_update_workspace_bytes.argtypes = [c_i32] * 7
 lib.dkv_attn_update.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp, c_sz, c_vp]
+lib.dkv_concat_reorder.argtypes = [c_vp] * 7 + [c_i32] * 6 + [c_vp]
 lib.dkv_gemm_workspace_bytes.restype = c_sz
 lib.dkv_gemm_workspace_bytes.argtypes = [c_i32] * 4
 lib.dkv_gemm.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_sz, c_vp]
@@ -285,6 +286,17 @@ def attn_update(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, 
                                _ptr(active_off), _ptr(out), rows, max_rows_per_seq, B, Hq, Hkv, L, dh, dtype,
                                _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
                                _stream()))
+
+
+def concat_reorder(k_cached, v_cached, k_new, v_new, take, dtype):
+    """The compact-layout cache operator of Appendix A: gather of concat(cached, new) rows by `take`."""
+    B, H, n_c, dh = k_cached.shape
+    n_n = k_new.shape[2]
+    k_out = torch.empty((B, H, n_c + n_n, dh), dtype=k_cached.dtype, device=k_cached.device)
+    v_out = torch.empty_like(k_out)
+    _check(lib.dkv_concat_reorder(_ptr(k_cached), _ptr(v_cached), _ptr(k_new), _ptr(v_new), _ptr(take), _ptr(k_out),
+                                  _ptr(v_out), B, H, n_c, n_n, dh, dtype, _stream()))
+    return k_out, v_out
 
 
 GEMM_OPT_STAGGER, GEMM_OPT_XCD_GROUP = 1, 2

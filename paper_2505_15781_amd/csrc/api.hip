@@ -579,6 +579,21 @@ extern "C" int dkv_attn_update(void *k_cache, void *v_cache, const void *q, cons
                                 head_dim, rows, p, workspace, AttnFusedUpdate{nullptr, nullptr, nullptr}, s);
 }
 
+extern "C" int dkv_concat_reorder(const void *k_cached, const void *v_cached, const void *k_new, const void *v_new,
+                                  const int32_t *take, void *k_out, void *v_out, int32_t batch, int32_t n_kv_heads,
+                                  int32_t n_cached, int32_t n_new, int32_t head_dim, int32_t dtype, void *stream) {
+    if (batch < 1 || n_kv_heads < 1 || n_cached < 0 || n_new < 0 || head_dim < 1 ||
+        (dtype != DKV_BF16 && dtype != DKV_FP32)) { dkv_set_error("bad argument"); return DKV_E_INVALID_ARG; }
+    if (n_cached + n_new == 0) return DKV_OK;
+    if (!take || !k_out || !v_out || (n_cached && (!k_cached || !v_cached)) || (n_new && (!k_new || !v_new))) {
+        dkv_set_error("null argument"); return DKV_E_INVALID_ARG;
+    }
+    const int row_bytes = head_dim * (dtype == DKV_BF16 ? 2 : 4);
+    if (row_bytes % 16) { dkv_set_error("a row of head_dim %d elements is not a multiple of 16 bytes", head_dim); return DKV_E_UNSUPPORTED; }
+    return dkv_launch_concat_reorder(static_cast<hipStream_t>(stream), k_cached, v_cached, k_new, v_new, take, k_out,
+                                     v_out, batch, n_kv_heads, n_cached, n_new, row_bytes);
+}
+
 extern "C" size_t dkv_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t dtype) {
     if (m < 1 || n < 1 || k < 1) return 0;
     GemmPlan p = dkv_gemm_plan(dtype, m, n, k);

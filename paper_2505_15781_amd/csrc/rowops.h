@@ -59,6 +59,9 @@ int dkv_launch_init_state(hipStream_t s, int *tokens, uint8_t *masked, int *stam
                           int batch, int L, int P, int k, int mask_id);
 int dkv_launch_fill_i32(hipStream_t s, int *p, int v, size_t n);
 int dkv_launch_fill_u8(hipStream_t s, uint8_t *p, uint8_t v, size_t n);
+int dkv_launch_concat_reorder(hipStream_t s, const void *k_cached, const void *v_cached, const void *k_new,
+                              const void *v_new, const int *take, void *k_out, void *v_out, int batch, int heads,
+                              int n_cached, int n_new, int row_bytes);
 int dkv_launch_scatter_rows(int dtype, hipStream_t s, int rows, const void *k_new, const void *v_new,
                             const int *idx, const int *off, void *Kc, void *Vc, int batch, int Hkv, int L,
                             int dh);

@@ -484,6 +484,36 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const T *__restrict__
     }
 }
 
+// The cache operator of Appendix A (concat_reorder), as an alternative layout to measure against: the
+// compact cache rows and the freshly computed rows of a (sequence, head) are concatenated and gathered into the
+// order given by `take` (the next step's cached rows first). 16-byte chunks, one per thread.
+__global__ __launch_bounds__(256) void concat_reorder_kernel(const uint4 *__restrict__ k_cached,
+                                                             const uint4 *__restrict__ v_cached,
+                                                             const uint4 *__restrict__ k_new,
+                                                             const uint4 *__restrict__ v_new,
+                                                             const int *__restrict__ take,
+                                                             uint4 *__restrict__ k_out, uint4 *__restrict__ v_out,
+                                                             int n_cached, int n_new, int cpr) {
+    const int L = n_cached + n_new;
+    const int bh = blockIdx.y, b = blockIdx.z;                 // head, sequence
+    const int H = gridDim.y;
+    const long c = (long)blockIdx.x * 256 + threadIdx.x;       // chunk of this (sequence, head)
+    if (c >= (long)L * cpr) return;
+    const int row = (int)(c / cpr), ch = (int)(c % cpr);
+    const int src = take[(size_t)b * L + row];
+    const size_t pair = (size_t)b * H + bh;
+    const uint4 *ks, *vs;
+    if (src < n_cached) {
+        ks = k_cached + (pair * n_cached + src) * cpr + ch;
+        vs = v_cached + (pair * n_cached + src) * cpr + ch;
+    } else {
+        ks = k_new + (pair * n_new + (src - n_cached)) * cpr + ch;
+        vs = v_new + (pair * n_new + (src - n_cached)) * cpr + ch;
+    }
+    k_out[(pair * L + row) * cpr + ch] = *ks;
+    v_out[(pair * L + row) * cpr + ch] = *vs;
+}
+
 template <typename T> int vpt_dispatch_embed(hipStream_t s, int rows, int d, const T *embed, const int *tokens,
                                              const int *row_pos, const int *row_seq, const int *counts,
                                              const float *gain, float *h, T *a, int *stamp, int L, float eps,
@@ -647,6 +677,19 @@ int dkv_launch_fill_i32(hipStream_t s, int *p, int v, size_t n) {
 int dkv_launch_fill_u8(hipStream_t s, uint8_t *p, uint8_t v, size_t n) {
     if (!n) return DKV_OK;
     hipLaunchKernelGGL(fill_u8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, v, n);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_concat_reorder(hipStream_t s, const void *k_cached, const void *v_cached, const void *k_new,
+                              const void *v_new, const int *take, void *k_out, void *v_out, int batch, int heads,
+                              int n_cached, int n_new, int row_bytes) {
+    const int L = n_cached + n_new, cpr = row_bytes / 16;
+    if (L <= 0 || batch <= 0) return DKV_OK;
+    dim3 grid((unsigned)(((long)L * cpr + 255) / 256), heads, batch);
+    hipLaunchKernelGGL(concat_reorder_kernel, grid, dim3(256), 0, s, (const uint4 *)k_cached, (const uint4 *)v_cached,
+                       (const uint4 *)k_new, (const uint4 *)v_new, take, (uint4 *)k_out, (uint4 *)v_out, n_cached,
+                       n_new, cpr);
     DKV_LAUNCH_CHECK();
     return DKV_OK;
 }

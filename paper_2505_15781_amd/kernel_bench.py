@@ -21,12 +21,16 @@ def main():
     ap.add_argument("--rows", default="2,32,64,128,192,256,512")
     ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--layout-alternative", action="store_true",
+                    help="instead: time the compact-layout concat_reorder operator of the paper's Appendix A per layer-step")
     args = ap.parse_args()
     import torch
     import dkv_inputs as D
     from paper_2505_15781_amd import binding
     from paper_2505_15781_amd.binding import lib, _ptr, _stream, _check
 
+    if args.layout_alternative:
+        return layout_alternative(torch, binding)
     model = D.model_run(args.config)[0]
     d, F = model.d_model, model.d_ffn
     shapes = {"qkv": (model.qkv_rows, d), "o": (d, model.n_q_heads * model.head_dim), "gate_up": (2 * F, d),
@@ -68,6 +72,41 @@ def main():
                   f"{nbytes / us * 1e-3:7.0f} GB/s {2.0 * M * N * K / us * 1e-6:7.1f} TFLOP/s", flush=True)
         del Ws
         torch.cuda.empty_cache()
+
+
+def layout_alternative(torch, binding):
+    """One layer-step of concat_reorder at the four workloads' cache shapes (cached rows of every sequence and
+    head are copied into the next order), over rotating buffers larger than the last-level cache."""
+    torch.cuda.set_device(0)
+    shapes = {"configs[1] A=8": (8, 32, 1024, 8), "configs[2] step 128": (1, 32, 512, 129),
+              "configs[3] greedy step": (4, 32, 1536, 7), "configs[4] step 128": (16, 4, 768, 129)}
+    g = torch.Generator(device="cuda").manual_seed(2)
+    for name, (B, H, L, n_new) in shapes.items():
+        n_c = L - n_new
+        per = 2 * B * H * L * 128 * 2
+        nbuf = max(2, int(600e6 // per) + 1)
+        bufs = [tuple(torch.randn((B, H, n, 128), generator=g, device="cuda").to(torch.bfloat16)
+                      for n in (n_c, n_c, n_new, n_new)) for _ in range(nbuf)]
+        take = torch.stack([torch.randperm(L, generator=g, device="cuda") for _ in range(B)]).to(torch.int32)
+        for kc, vc, kn, vn in bufs:
+            binding.concat_reorder(kc, vc, kn, vn, take, binding.BF16)
+        torch.cuda.synchronize()
+        k_out = torch.empty((B, H, L, 128), dtype=torch.bfloat16, device="cuda")
+        v_out = torch.empty_like(k_out)
+        from paper_2505_15781_amd.binding import lib, _ptr, _stream, _check
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        reps = 10
+        for _ in range(reps):
+            for kc, vc, kn, vn in bufs:
+                _check(lib.dkv_concat_reorder(_ptr(kc), _ptr(vc), _ptr(kn), _ptr(vn), _ptr(take), _ptr(k_out),
+                                              _ptr(v_out), B, H, n_c, n_new, 128, binding.BF16, _stream()))
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * nbuf)
+        print(f"{name:24s} B={B:2d} Hkv={H:2d} L={L:5d} new rows {n_new:4d}: {us:7.1f} us per layer-step, "
+              f"{2 * per / us * 1e-3:6.0f} GB/s read+write; the position-indexed cache writes "
+              f"{2 * B * H * n_new * 256 / 1e3:.0f} KB in the RoPE kernel instead", flush=True)
 
 
 if __name__ == "__main__":

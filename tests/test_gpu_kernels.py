@@ -175,6 +175,35 @@ def test_attention_microbenchmark_configuration_full_size(n_active):
     _attn_case(D.CONFIG1_SHAPE, n_active, 1100 + D.CONFIG1_ACTIVE_SIZES.index(n_active))
 
 
+@pytest.mark.parametrize("dtype", [BF16, FP32])
+def test_concat_reorder_operator_reproduces_the_compact_layout(dtype):
+    """The paper's cache operator (Appendix A) on its compact layout, bit for bit: cached rows left, new rows
+    right, gathered into the next step's order given by the oracle's index bookkeeping (which the worked
+    example of the appendix pins)."""
+    import paper_2505_15781_amd as P
+    from oracle import schedule as S
+    B, H, L, dh = 3, 2, 23, 64
+    rng = np.random.default_rng(5)
+    full_k = D.normal_f32(12, 1, (B, H, L, dh), bf16=dtype == BF16)      # K/V of every position, position order
+    full_v = D.normal_f32(12, 2, (B, H, L, dh), bf16=dtype == BF16)
+    n_c = 9
+    kc, vc, kn, vn, take, want_k, want_v = [], [], [], [], [], [], []
+    for b in range(B):
+        unm_prev = sorted(rng.choice(L, size=n_c, replace=False).tolist())            # cached at this step
+        rest = [p for p in range(L) if p not in unm_prev]
+        unm_next = sorted(unm_prev + rng.choice(rest, size=2, replace=False).tolist())   # two more next step
+        layout_prev, layout_next, mapping, _ = S.reorder_map(unm_prev, unm_next, L)
+        kc.append(full_k[b][:, layout_prev[:n_c]]); vc.append(full_v[b][:, layout_prev[:n_c]])
+        kn.append(full_k[b][:, layout_prev[n_c:]]); vn.append(full_v[b][:, layout_prev[n_c:]])
+        take.append(mapping)
+        want_k.append(full_k[b][:, layout_next]); want_v.append(full_v[b][:, layout_next])
+    dev = lambda xs: _dev(np.stack(xs), dtype)
+    tk = torch.tensor(np.asarray(take, dtype=np.int32), device="cuda")
+    ko, vo = P.concat_reorder(dev(kc), dev(vc), dev(kn), dev(vn), tk, dtype)
+    assert np.array_equal(ko.float().cpu().numpy(), np.stack(want_k))
+    assert np.array_equal(vo.float().cpu().numpy(), np.stack(want_v))
+
+
 def test_bad_arguments_are_errors_not_faults():
     import paper_2505_15781_amd as P
     shape = D.AttnUpdateShape(batch=1, n_q_heads=2, n_kv_heads=1, seq_len=40, head_dim=48, dtype=BF16)
