@@ -54,3 +54,27 @@ def test_bench_refuses_more_than_one_gpu():
     import subprocess, sys
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert res.returncode != 0 and "one GPU" in res.stderr
+
+
+def test_projection_and_attention_planners_return_sane_workspace_sizes_without_a_gpu():
+    """The planners are host code: every (rows, shape) gets a K split from the documented set (the workspace is
+    that many fp32 copies of the output), and the attention workspace never exceeds one partial record per
+    (row, head, key slice) with at most seq_len / 64 slices."""
+    from paper_2505_15781_amd import binding as b
+    shapes = [(12288, 4096), (4096, 4096), (24576, 4096), (4096, 12288), (4608, 3584), (37888, 3584),
+              (3584, 18944), (126464, 4096), (384, 128), (200, 136)]
+    for n, k in shapes:
+        for m in (1, 2, 17, 64, 65, 128, 129, 257, 512, 777, 1536, 4112, 12288):
+            nb = b.lib.dkv_gemm_workspace_bytes(m, n, k, b.BF16)
+            assert nb % (4 * m * n) == 0
+            assert nb // (4 * m * n) in (0, 2, 3, 4, 6, 8), (m, n, k, nb)
+            assert b.lib.dkv_gemm_workspace_bytes(m, n, k, b.FP32) == 0
+    assert b.lib.dkv_gemm_workspace_bytes(0, 128, 64, b.BF16) == 0
+    for (B, hq, hkv, L, dh) in [(8, 32, 32, 1024, 128), (1, 32, 32, 512, 128), (4, 32, 32, 1536, 128),
+                                (16, 28, 4, 768, 128), (3, 6, 2, 203, 64), (1, 4, 2, 2085, 128)]:
+        for rows in (1, 5, 16, 64, 257, L):
+            nb = b.lib.dkv_attn_update_workspace_bytes(B, hq, hkv, L, dh, b.BF16, rows)
+            g = hq // hkv
+            rows_pad = -(-(-(-rows * g // 16) * 16) // g)
+            assert nb <= B * rows_pad * hq * max(1, L // 64) * (dh + 4) * 4, (B, hq, hkv, L, dh, rows, nb)
+        assert b.lib.dkv_attn_update_workspace_bytes(B, hq, hkv, L, dh, b.FP32, 8) <= 256     # no partial records
