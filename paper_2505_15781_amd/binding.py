@@ -299,14 +299,17 @@ def concat_reorder(k_cached, v_cached, k_new, v_new, take, dtype):
     return k_out, v_out
 
 
-GEMM_OPT_STAGGER, GEMM_OPT_XCD_GROUP = 1, 2
+GEMM_OPT_STAGGER, GEMM_OPT_XCD_GROUP, GEMM_OPT_SWIGLU = 1, 2, 4
 
 
 def gemm(x, w, dtype, kind=None, split_k=1, options=0):
     """y = x @ w.T in fp32 through the library's projection kernel (heuristic choice unless `kind`)."""
     m, k = x.shape
     n = w.shape[0]
-    y = torch.empty((m, n), dtype=torch.float32, device=x.device)
+    if options & GEMM_OPT_SWIGLU:          # fused epilogue: [m, n/2] in the input dtype
+        y = torch.empty((m, n // 2), dtype=x.dtype, device=x.device)
+    else:
+        y = torch.empty((m, n), dtype=torch.float32, device=x.device)
     if kind is None:
         nb = lib.dkv_gemm_workspace_bytes(m, n, k, dtype)
         ws = torch.empty(max(nb, 4), dtype=torch.uint8, device=x.device)

@@ -401,8 +401,14 @@ extern "C" int dkv_denoise_step(dkv_ctx *c, int32_t step, const int32_t *forced_
         if ((rc = dkv_launch_residual_norm(dt, s, rows, d, c->part, p.split_k, (size_t)rows * d, c->counts, c->n2[l],
                                            c->h, c->a, m.rms_eps))) return rc;
         p = dkv_gemm_plan(dt, rows, 2 * m.d_ffn, d);
-        if ((rc = timed_gemm(c, c->a, c->wgu[l], c->part, rows, n_rows, 2 * m.d_ffn, d, p))) return rc;
-        if ((rc = dkv_launch_swiglu(dt, s, rows, c->part, p.split_k, (size_t)rows * 2 * m.d_ffn, c->counts, c->f, m.d_ffn))) return rc;
+        if (dkv_gemm_can_fuse_swiglu(dt, 2 * m.d_ffn, d, p)) {
+            // single K slice: SwiGLU in the projection's epilogue, the fp32 gate/up product is never written
+            p.flags |= GEMM_FLAG_SWIGLU;
+            if ((rc = timed_gemm(c, c->a, c->wgu[l], reinterpret_cast<float *>(c->f), rows, n_rows, 2 * m.d_ffn, d, p))) return rc;
+        } else {
+            if ((rc = timed_gemm(c, c->a, c->wgu[l], c->part, rows, n_rows, 2 * m.d_ffn, d, p))) return rc;
+            if ((rc = dkv_launch_swiglu(dt, s, rows, c->part, p.split_k, (size_t)rows * 2 * m.d_ffn, c->counts, c->f, m.d_ffn))) return rc;
+        }
         p = dkv_gemm_plan(dt, rows, d, m.d_ffn);
         if ((rc = timed_gemm(c, c->f, c->wdown[l], c->part, rows, n_rows, d, m.d_ffn, p))) return rc;
         const float *next_gain = (l + 1 < m.n_layers) ? c->n1[l + 1] : c->final_norm;
@@ -600,11 +606,12 @@ extern "C" size_t dkv_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int3
     return p.split_k > 1 ? (size_t)p.split_k * m * n * 4 : 0;
 }
 
-extern "C" int dkv_gemm_with(const void *x, const void *w, float *y, int32_t m, int32_t n, int32_t k, int32_t dtype,
+extern "C" int dkv_gemm_with(const void *x, const void *w, void *yv, int32_t m, int32_t n, int32_t k, int32_t dtype,
                              int32_t kind, int32_t split_k, int32_t options, void *workspace,
                              size_t workspace_bytes, void *stream) {
+    float *y = static_cast<float *>(yv);
     if (!x || !w || !y || m < 1 || n < 1 || k < 1) { dkv_set_error("bad argument"); return DKV_E_INVALID_ARG; }
-    if (options & ~(DKV_GEMM_OPT_STAGGER | DKV_GEMM_OPT_XCD_GROUP)) {
+    if (options & ~(DKV_GEMM_OPT_STAGGER | DKV_GEMM_OPT_XCD_GROUP | DKV_GEMM_OPT_SWIGLU)) {
         dkv_set_error("unknown projection option bits 0x%x", options);
         return DKV_E_INVALID_ARG;
     }
@@ -615,6 +622,13 @@ extern "C" int dkv_gemm_with(const void *x, const void *w, float *y, int32_t m, 
     p.frac_units = split_k < 0 ? (k / 64) * 3 / 4 : 0;      // split_k = -1 asks for the 3/4 share
     p.flags = ((options & DKV_GEMM_OPT_STAGGER) ? GEMM_FLAG_STAGGER : 0) |
               ((options & DKV_GEMM_OPT_XCD_GROUP) ? GEMM_FLAG_XCD_GROUP : 0);
+    if (options & DKV_GEMM_OPT_SWIGLU) {
+        if (!dkv_gemm_can_fuse_swiglu(dtype, n, k, p)) {
+            dkv_set_error("kernel %d with %d K slices cannot fuse SwiGLU (bf16 tile kernels, one K slice, even N)", kind, split_k);
+            return DKV_E_UNSUPPORTED;
+        }
+        p.flags |= GEMM_FLAG_SWIGLU;
+    }
     if (!dkv_gemm_plan_valid(dtype, k, p)) {
         dkv_set_error("kernel %d with %d K slices does not take dtype %d, K %d", kind, split_k, dtype, k);
         return DKV_E_UNSUPPORTED;

@@ -75,7 +75,7 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // Plan of one projection: tile shape and split of the K dimension.
 enum { GEMM_DMA_32x128 = 0, GEMM_DMA_64x128, GEMM_DMA_128x128, GEMM_DMA_128x256, GEMM_DMA_256x256,
        GEMM_DMA_128x96, GEMM_DMA_128x192, GEMM_DMA_256x192, GEMM_REG_64x128, GEMM_SIMT, GEMM_KINDS };
-enum { GEMM_FLAG_STAGGER = 1, GEMM_FLAG_XCD_GROUP = 2 };
+enum { GEMM_FLAG_STAGGER = 1, GEMM_FLAG_XCD_GROUP = 2, GEMM_FLAG_SWIGLU = 4 };
 struct GemmPlan {
     int kind;      // GEMM_* kernel and tile shape
     int split_k;   // number of partial slots: slice or part s writes partial[s]
@@ -87,6 +87,9 @@ int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p);
 
 // partial[s][m][n] (fp32, stride m_cap rows per slice) = A[m, k-slice] * W[n, k-slice]^T.
 // Rows >= *m_dev (when m_dev != nullptr) are neither read nor written.
+// With GEMM_FLAG_SWIGLU in plan.flags (gemm_dma kinds, one K slice, W rows interleaved gate_j, up_j): `partial` is
+// instead a bf16 [m][n/2] array that receives silu(gate_j) * up_j, and no fp32 product is written.
+bool dkv_gemm_can_fuse_swiglu(int dtype, int n, int k, const GemmPlan &p);
 int dkv_launch_gemm(int dtype, const void *A, const void *W, float *partial, int m_upper, int m_cap,
                     const int *m_dev, int n, int k, GemmPlan plan, hipStream_t stream);
 

@@ -179,6 +179,32 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));   // the clamped tail loads must land before LDS is reused
 
+    if (flags & GEMM_FLAG_SWIGLU) {
+        // Fused SwiGLU (single K slice only): output columns 2j (gate_j) and 2j+1 (up_j) sit in neighbouring
+        // lanes; each lane fetches its neighbour's value with a DPP quad permute, even lanes finish
+        // accumulator elements 0..7 and odd lanes 8..15, and f[m][j] = silu(gate) * up goes out as bf16.
+        bf16_t *f = reinterpret_cast<bf16_t *>(P);
+        const int F = N >> 1;
+        const bool odd = lane & 1;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int n = n0 + (wn * NT + j) * 32 + (lane & 31);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float own = acc[i][j][v];
+                    const float other = __builtin_bit_cast(
+                        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, own), 0xB1, 0xF, 0xF, true));
+                    if ((v < 8) != odd) {
+                        const float g = odd ? other : own, u = odd ? own : other;
+                        const float r = g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;
+                        const int m = m0 + (wm * MT + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                        if (m < M && n < N) f[(size_t)m * F + (n >> 1)] = f2bf(r);
+                    }
+                }
+            }
+    } else {
     float *out = P + (size_t)slot * m_cap * N;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -191,6 +217,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
                 if (m < M && n < N) out[(size_t)m * N + n] = acc[i][j][v];
             }
         }
+    }
     }   // m0 < M
     if (!frac_units || unit >= unit_end) break;
     __syncthreads();      // every wave is done with the LDS stages before the next part refills them
@@ -349,9 +376,17 @@ int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, c
     dim3 grid(ceil_div(n, BN), ceil_div(m_upper, BM), ceil_div(kt_total, kps));
     if (frac_units) {
         grid = dim3(ceil_div(grid.x * grid.y * kt_total, frac_units), 1, 1);
+        if (flags & GEMM_FLAG_SWIGLU) {
+            dkv_set_error("the fused SwiGLU epilogue needs one K slice");
+            return DKV_E_INVALID_ARG;
+        }
         flags = 0;
     }
     if ((grid.x * grid.y * grid.z) % 8 != 0 || grid.y < 4) flags &= ~GEMM_FLAG_XCD_GROUP;
+    if ((flags & GEMM_FLAG_SWIGLU) && (grid.z != 1 || (n & 1))) {
+        dkv_set_error("the fused SwiGLU epilogue needs one K slice and an even number of columns");
+        return DKV_E_INVALID_ARG;
+    }
     hipLaunchKernelGGL((gemm_dma<MT, NT, WM, WN, STAGES>), grid, dim3(64 * WM * WN), smem, s, (const bf16_t *)A,
                        (const bf16_t *)W, P, m_upper, m_cap, m_dev, n, k, kps, frac_units, flags);
     DKV_LAUNCH_CHECK();
@@ -436,6 +471,11 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     // Giving 256 workgroups 3/4 of a tile's K range each (frac_units, kept for experiments through
     // dkv_gemm_with) was measured to take the same time as two full slices, so it is never planned.
     return p;
+}
+
+bool dkv_gemm_can_fuse_swiglu(int dtype, int n, int k, const GemmPlan &p) {
+    return dtype == DKV_BF16 && p.kind <= GEMM_DMA_256x192 && p.split_k == 1 && p.frac_units == 0 && (k % BK) == 0 &&
+           (n & 1) == 0;
 }
 
 int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p) {

@@ -65,12 +65,32 @@ def test_projection_launch_options_leave_the_product_unchanged(kind, options, m,
     check_close(y, x.astype(np.float64) @ w.astype(np.float64).T, 1e-5, f"{kind} options {options} {m}x{n}x{k}")
 
 
+@pytest.mark.parametrize("kind", ["dma_32x128", "dma_64x128", "dma_128x128", "dma_128x256", "dma_256x256",
+                                  "dma_128x96", "dma_128x192", "dma_256x192"])
+@pytest.mark.parametrize("m,n,k", [(5, 128, 256), (129, 392, 1024), (300, 520, 768)])
+def test_projection_with_fused_swiglu_epilogue(kind, m, n, k):
+    """Rows of w interleave gate_j, up_j; the epilogue writes silu(gate) * up (the feed-forward's activation)
+    as bf16 [m, n/2] instead of the fp32 product. bf16 output: one rounding, 2^-9 relative."""
+    import paper_2505_15781_amd as P
+    from paper_2505_15781_amd import binding
+    x = D.normal_f32(10, 1, (m, k), bf16=True)
+    w = D.normal_f32(10, 2, (n, k), std=0.05, bf16=True)
+    y = P.gemm(_dev(x, BF16), _dev(w, BF16), BF16, kind=kind, split_k=1,
+               options=binding.GEMM_OPT_SWIGLU).float().cpu().numpy()
+    prod = x.astype(np.float64) @ w.astype(np.float64).T
+    g, u = prod[:, 0::2], prod[:, 1::2]
+    check_close(y, g / (1.0 + np.exp(-g)) * u, 4e-3, f"{kind} fused swiglu {m}x{n}x{k}")
+    with pytest.raises(P.DkvError) as e:
+        P.gemm(_dev(x, BF16), _dev(w, BF16), BF16, kind=kind, split_k=2, options=binding.GEMM_OPT_SWIGLU)
+    assert e.value.code == -3
+
+
 def test_projection_rejects_unknown_option_bits():
     import paper_2505_15781_amd as P
     x = _dev(D.normal_f32(6, 1, (4, 64), bf16=True), BF16)
     w = _dev(D.normal_f32(6, 2, (8, 64), bf16=True), BF16)
     with pytest.raises(P.DkvError) as e:
-        P.gemm(x, w, BF16, kind="dma_32x128", split_k=1, options=8)
+        P.gemm(x, w, BF16, kind="dma_32x128", split_k=1, options=16)
     assert e.value.code == -1
 
 
