@@ -79,9 +79,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
         if (flags & GEMM_FLAG_XCD_GROUP) {
             // position of this workgroup in the order "XCD 0's share, XCD 1's share, ..." of the sequence
             // (K slice, group of 4 tile rows, tile column, tile row within the group)
-            const int gx = gridDim.x, gy = gridDim.y, total = gx * gy * gridDim.z;   // host: total % 8 == 0
+            const int gx = gridDim.x, gy = gridDim.y, total = gx * gy * gridDim.z;
             const int id = bx + gx * (by + gy * bz);
-            const int pos = (id & 7) * (total >> 3) + (id >> 3);
+            // XCD x runs the ids x, x + 8, ...: total / 8 of them, one more for x < total % 8
+            const int pos = (id & 7) * (total >> 3) + min(id & 7, total & 7) + (id >> 3);
             bz = pos / (gx * gy);
             const int p2 = pos - bz * gx * gy;
             const int grp = p2 / (4 * gx), within = p2 - grp * 4 * gx;
@@ -382,7 +383,7 @@ int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, c
         }
         flags = 0;
     }
-    if ((grid.x * grid.y * grid.z) % 8 != 0 || grid.y < 4) flags &= ~GEMM_FLAG_XCD_GROUP;
+    if (grid.y < 4) flags &= ~GEMM_FLAG_XCD_GROUP;
     if ((flags & GEMM_FLAG_SWIGLU) && (grid.z != 1 || (n & 1))) {
         dkv_set_error("the fused SwiGLU epilogue needs one K slice and an even number of columns");
         return DKV_E_INVALID_ARG;
