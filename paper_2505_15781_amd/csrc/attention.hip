@@ -203,6 +203,7 @@ AttnPlan dkv_attn_plan(int dtype, int batch, int n_q_heads, int n_kv_heads, int 
     AttnPlan p;
     p.use_mfma = (dtype == DKV_BF16 && (head_dim == 64 || head_dim == 128)) ? 1 : 0;
     p.shared_nq = 0;
+    p.shared_waves = 0;
     p.q_blocks = 0;
     p.ksplit_nq = 0;
     p.ksplit_waves = 0;
@@ -223,7 +224,12 @@ AttnPlan dkv_attn_plan(int dtype, int batch, int n_q_heads, int n_kv_heads, int 
     const bool shared = head_dim == 128 && p.q_tiles >= 5 && (long)batch * n_kv_heads * blocks8 >= 192;
     int s = 1, n_tiles, min_tiles;
     if (shared) {
-        p.shared_nq = 2;
+        // Blocks of 8 query tiles either way. With fewer than two workgroups per compute unit, 8 wavefronts
+        // with one query tile each: a second wavefront per SIMD fills the waits of the first (softmax between
+        // the two products, the tile barrier), which two co-resident workgroups do otherwise.
+        const bool wide = (long)batch * n_kv_heads * blocks8 < 512;
+        p.shared_nq = wide ? 1 : 2;
+        p.shared_waves = wide ? 8 : 4;
         p.q_blocks = blocks8;
         n_tiles = ceil_div(seq_len, 64);
         min_tiles = 2;
@@ -332,14 +338,20 @@ int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache,
         const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_blocks * plan.splits);
         static bool lds_ok = false;
         if (!lds_ok) {
-            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2>),
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2, 4>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1, 8>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
             lds_ok = true;
         }
-        hipLaunchKernelGGL((attn_bf16_shared<2>), dim3(wgs), dim3(256), smem, stream, (const bf16_t *)q,
-                           (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out,
-                           (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits,
-                           plan.tiles_per_split, rows_upper, scale_log2e);
+#define SHARED(NQ_, NW_)                                                                                          \
+    hipLaunchKernelGGL((attn_bf16_shared<NQ_, NW_>), dim3(wgs), dim3(64 * NW_), smem, stream, (const bf16_t *)q,  \
+                       (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out, (float *)partial, \
+                       batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits, plan.tiles_per_split,    \
+                       rows_upper, scale_log2e)
+        if (plan.shared_waves == 8) SHARED(1, 8);
+        else SHARED(2, 4);
+#undef SHARED
         DKV_LAUNCH_CHECK();
         if (plan.splits > 1) {
             hipLaunchKernelGGL((attn_merge<128>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream,

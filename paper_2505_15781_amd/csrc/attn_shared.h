@@ -1,16 +1,16 @@
-// Attention kernel for larger active sets: the four wavefronts of a workgroup share each K/V tile.
+// Attention kernel for larger active sets: the NW (4 or 8) wavefronts of a workgroup share each K/V tile.
 // Included by attention.hip (uses its helpers); head_dim 128 only.
 //
-// Work item = (sequence, kv head, block of 4*NQ query tiles of 16 rows, key slice). The workgroup
+// Work item = (sequence, kv head, block of NW*NQ query tiles of 16 rows, key slice). The workgroup
 // streams its key slice in tiles of 64 keys: every thread fetches part of the K rows and of the V rows
-// as they are stored (transposing LDS reads form the V operand of the second product), two LDS stages alternate, and the next tile's global
-// loads are in flight while the current one is multiplied. Each wavefront multiplies its own NQ query
+// as they are stored (transposing LDS reads form the V operand of the second product), two LDS stages alternate, and the global
+// loads of the next tile (with 8 wavefronts: of the next two) are in flight while the current one is multiplied. Each wavefront multiplies its own NQ query
 // tiles against the shared tile, so a K or V fragment read from LDS feeds NQ MFMAs and the tile is read
 // from L2 once per 64*NQ query rows instead of once per 16.
 #pragma once
 
-template <int NQ>
-__global__ __launch_bounds__(256, 2) void attn_bf16_shared(
+template <int NQ, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_shared(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
     const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
     int Hq, int Hkv, int L, int q_blocks, int splits, int tiles_per_split, int rows_cap,
@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_shared(
 
     const int r0 = row_off[b], nrows = row_off[b + 1] - r0;
     const int nq = nrows * G;
-    const int mb0 = qb * 4 * NQ * 16;
+    const int mb0 = qb * NW * NQ * 16;
     if (mb0 >= nq) return;                       // uniform for the workgroup
 
     const int qi = lane & 15, g = lane >> 4;
@@ -58,24 +58,25 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_shared(
     const int n_tiles = (L + KT2 - 1) / KT2;
     const int t0 = split * tiles_per_split, t1 = min(n_tiles, t0 + tiles_per_split);
 
-    // per thread: 4 chunks (16 B) of K and of V
-    uint4 kreg[4], vreg[4];
-    auto load_tile = [&](int t) {
+    // per thread: CH chunks (16 B) of K and of V per tile, in register set A or B on their way to LDS
+    constexpr int NT = 64 * NW, CH = KT2 * (DH / 8) / NT;
+    uint4 kA[CH], vA[CH], kB[CH], vB[CH];
+    auto load_tile = [&](int t, uint4 (&kr)[CH], uint4 (&vr)[CH]) {
         const int key0 = t * KT2;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int c = tid + 256 * i, key = c >> 4, ch = c & 15, gk = key0 + key;
-            kreg[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
-            vreg[i] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < CH; ++i) {
+            const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = key0 + key;
+            kr[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+            vr[i] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
         }
     };
-    auto store_tile = [&](int stage) {
+    auto store_tile = [&](int stage, const uint4 (&kr)[CH], const uint4 (&vr)[CH]) {
         unsigned char *ksm = smem_raw + stage * STAGE_BYTES, *vsm = ksm + K_BYTES;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int c = tid + 256 * i, key = c >> 4, ch = c & 15;
-            *reinterpret_cast<uint4 *>(ksm + key * K_STRIDE + ch * 16) = kreg[i];
-            *reinterpret_cast<uint4 *>(vsm + key * V_STRIDE + ch * 16) = vreg[i];
+        for (int i = 0; i < CH; ++i) {
+            const int c = tid + NT * i, key = c >> 4, ch = c & 15;
+            *reinterpret_cast<uint4 *>(ksm + key * K_STRIDE + ch * 16) = kr[i];
+            *reinterpret_cast<uint4 *>(vsm + key * V_STRIDE + ch * 16) = vr[i];
         }
     };
     const int v_lane_off = (4 * g + (qi >> 2)) * V_STRIDE + (qi & 3) * 8;
@@ -90,14 +91,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_shared(
         for (int i = 0; i < DH / 16; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    if (t0 < t1) {
-        load_tile(t0);
-        store_tile(0);
-    }
-    __syncthreads();
-    for (int t = t0; t < t1; ++t) {
-        const int stage = (t - t0) & 1;
-        if (t + 1 < t1) load_tile(t + 1);
+    // products and softmax of tile t, which sits in LDS stage `stage`
+    auto multiply = [&](int t, int stage) {
         const unsigned char *ksm = smem_raw + stage * STAGE_BYTES, *vsm = ksm + K_BYTES;
         f32x4 st[NQ][4];
 #pragma unroll
@@ -130,8 +125,40 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_shared(
                 for (int j = 0; j < NQ; ++j)
                     acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[j][hh], acc[j][mt], 0, 0, 0);
             }
-        if (t + 1 < t1) store_tile(stage ^ 1);
+    };
+
+    // Tile t0 + i is multiplied out of LDS stage i & 1. t0 and t1 are uniform for the workgroup, so every
+    // wavefront passes the same barriers.
+    if (t0 < t1) {
+        load_tile(t0, kA, vA);
+        store_tile(0, kA, vA);
+    }
+    if (NW == 8) {
+        // one workgroup per compute unit: while a tile is multiplied, the next one waits in one register set
+        // and the one after it is being fetched into the other (16 registers per set)
+        if (t0 + 1 < t1) load_tile(t0 + 1, kA, vA);
         __syncthreads();
+        for (int t = t0; t < t1; t += 2) {
+            if (t + 2 < t1) load_tile(t + 2, kB, vB);
+            multiply(t, 0);
+            if (t + 1 < t1) store_tile(1, kA, vA);
+            __syncthreads();
+            if (t + 1 >= t1) break;
+            if (t + 3 < t1) load_tile(t + 3, kA, vA);
+            multiply(t + 1, 1);
+            if (t + 2 < t1) store_tile(0, kB, vB);
+            __syncthreads();
+        }
+    } else {
+        // two workgroups per compute unit cover each other's waits: one tile ahead is enough
+        __syncthreads();
+        for (int t = t0; t < t1; ++t) {
+            const int stage = (t - t0) & 1;
+            if (t + 1 < t1) load_tile(t + 1, kA, vA);
+            multiply(t, stage);
+            if (t + 1 < t1) store_tile(stage ^ 1, kA, vA);
+            __syncthreads();
+        }
     }
 
 #pragma unroll

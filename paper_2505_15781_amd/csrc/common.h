@@ -99,7 +99,8 @@ struct AttnPlan {
     int splits;       // slices of the key range
     int tiles_per_split;   // in tiles of 32 keys (wave-private kernel) or 64 keys (shared kernel)
     int shared_nq;    // 0: one wavefront per item; 1 or 2: workgroup-shared K/V tiles, query tiles per wavefront
-    int q_blocks;     // shared kernel: blocks of 4 * shared_nq query tiles
+    int shared_waves; // shared kernel: wavefronts per workgroup (4 or 8)
+    int q_blocks;     // shared kernel: blocks of shared_waves * shared_nq query tiles
     int ksplit_nq;    // 0, or 1 / 2: key-split kernel (wavefronts of a workgroup share the keys), query tiles per item
     int ksplit_waves; // key-split kernel: wavefronts per workgroup (4 or 8)
     int q_groups;     // key-split kernel: groups of ksplit_nq query tiles

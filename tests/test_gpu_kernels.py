@@ -168,6 +168,17 @@ def test_attention_many_query_tiles_per_head():
     _attn_case(shape, 66, 37)
 
 
+@pytest.mark.parametrize("seq_len", [64, 100, 192, 300, 512])
+def test_attention_shared_tiles_eight_wavefronts(seq_len):
+    """Fewer than two workgroups per compute unit for the shared-tile kernel (4 x 16 kv heads x 5 blocks = 320):
+    its 8-wavefront form, which keeps two tiles on their way. Key counts of 1, 2 (ragged), 3, 5 (ragged) and 8
+    tiles take both exits of its two-tile loop; 66 rows leave the last block almost empty."""
+    shape = D.AttnUpdateShape(batch=4, n_q_heads=128, n_kv_heads=16, seq_len=seq_len, head_dim=128, dtype=BF16)
+    n = min(79, seq_len)
+    _attn_case(shape, n, 44)
+    _attn_case(shape, min(66, seq_len), 45)
+
+
 @pytest.mark.parametrize("dh", [128, 64])
 def test_attention_many_small_items(dh):
     """More (sequence, head, query group) items than compute units: the key-split kernel in its
