@@ -21,6 +21,9 @@ def main():
     ap.add_argument("--rows", default="2,32,64,128,192,256,512")
     ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--attention", default=None, metavar="ROWS",
+                    help="instead: time cache update + attention at the configs[1] shape for these active rows per "
+                         "sequence (e.g. 1,8,32,128,512), over rotating caches larger than the last-level cache")
     ap.add_argument("--layout-alternative", action="store_true",
                     help="instead: time the compact-layout concat_reorder operator of the paper's Appendix A per layer-step")
     args = ap.parse_args()
@@ -31,6 +34,8 @@ def main():
 
     if args.layout_alternative:
         return layout_alternative(torch, binding)
+    if args.attention:
+        return attention(torch, D, [int(a) for a in args.attention.split(",")], args.reps)
     model = D.model_run(args.config)[0]
     d, F = model.d_model, model.d_ffn
     shapes = {"qkv": (model.qkv_rows, d), "o": (d, model.n_q_heads * model.head_dim), "gate_up": (2 * F, d),
@@ -72,6 +77,40 @@ def main():
                   f"{nbytes / us * 1e-3:7.0f} GB/s {2.0 * M * N * K / us * 1e-6:7.1f} TFLOP/s", flush=True)
         del Ws
         torch.cuda.empty_cache()
+
+
+def attention(torch, D, sizes, reps):
+    """dkv_attn_update at B=8, 32 heads x 128, L=1024: per call the 134 MB of K/V are read once from HBM."""
+    import paper_2505_15781_amd as P
+    torch.cuda.set_device(0)
+    shape = D.CONFIG1_SHAPE
+    B, H, L, dh = shape.batch, shape.n_q_heads, shape.seq_len, shape.head_dim
+    nbuf = 5
+    g = torch.Generator(device="cuda").manual_seed(1100)
+    kc = [torch.randn((B, H, L, dh), generator=g, device="cuda").to(torch.bfloat16) for _ in range(nbuf)]
+    vc = [torch.randn((B, H, L, dh), generator=g, device="cuda").to(torch.bfloat16) for _ in range(nbuf)]
+    for i, A in enumerate(sizes):
+        c = D.attn_update_case(D.AttnUpdateShape(B, 1, 1, L, 2), A, 1100 + i)     # positions only
+        idx, off = torch.from_numpy(c["active_idx"]).cuda(), torch.from_numpy(c["active_off"]).cuda()
+        R = B * A
+        q, kn, vn = (torch.randn((R, H, dh), generator=g, device="cuda").to(torch.bfloat16) for _ in range(3))
+        o = torch.empty_like(q)
+        ws = torch.empty(max(P.attn_update_workspace_bytes(B, H, H, L, dh, P.BF16, A), 256), dtype=torch.uint8,
+                         device="cuda")
+        for j in range(nbuf):
+            P.attn_update(kc[j], vc[j], q, kn, vn, idx, off, o, R, A, P.BF16, ws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            for j in range(nbuf):
+                P.attn_update(kc[j], vc[j], q, kn, vn, idx, off, o, R, A, P.BF16, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * nbuf)
+        nbytes = 2 * B * H * L * dh * 2 + 6 * R * H * dh * 2
+        print(f"active rows {A:4d}: {us:8.1f} us {nbytes / us * 1e-3:7.0f} GB/s "
+              f"{4.0 * R * H * L * dh / us * 1e-6:7.1f} TFLOP/s", flush=True)
 
 
 def layout_alternative(torch, binding):
