@@ -116,9 +116,10 @@ def test_projection_kernel_rejects_shapes_it_cannot_take():
     check_close(y, x.float().cpu().numpy().astype(np.float64) @ w.float().cpu().numpy().astype(np.float64).T, 1e-5, "reg")
 
 
-def _attn_case(shape, n_active, seed, ragged=None):
+def _attn_case(shape, n_active, seed, ragged=None, q_scale=1.0):
     import paper_2505_15781_amd as P
     c = D.attn_update_case(shape, n_active, seed, ragged=ragged)
+    c["q"] = c["q"] * np.float32(q_scale)            # a power of two: still exact bfloat16 values
     dt = shape.dtype
     kc, vc = _dev(c["k_cache"], dt), _dev(c["v_cache"], dt)
     rows = int(c["active_off"][-1])
@@ -185,6 +186,21 @@ def test_attention_many_small_items(dh):
     4-wavefront form, two workgroups per compute unit, with the cache update fused (40 rows per sequence)."""
     shape = D.AttnUpdateShape(batch=20, n_q_heads=16, n_kv_heads=16, seq_len=150, head_dim=dh, dtype=BF16)
     _attn_case(shape, 40, 38)
+
+
+@pytest.mark.parametrize("q_scale", [16.0, 0.0])
+def test_attention_peaked_and_flat_softmax(q_scale):
+    """Scores with a standard deviation of 16 (after the 1/sqrt(d_h)): almost one-hot probabilities, running maxima
+    that keep rising over the key tiles and rescale the output; and all-zero queries: every key weighs the same, the
+    output is the mean of V. Through the key-split, both shared-tile and the generic kernels."""
+    _attn_case(D.AttnUpdateShape(batch=2, n_q_heads=4, n_kv_heads=2, seq_len=1031, head_dim=128, dtype=BF16),
+               None, 46, ragged=[3, 40], q_scale=q_scale)
+    _attn_case(D.AttnUpdateShape(batch=4, n_q_heads=128, n_kv_heads=16, seq_len=300, head_dim=128, dtype=BF16),
+               79, 47, q_scale=q_scale)
+    _attn_case(D.AttnUpdateShape(batch=16, n_q_heads=128, n_kv_heads=16, seq_len=200, head_dim=128, dtype=BF16),
+               66, 48, q_scale=q_scale)
+    _attn_case(D.AttnUpdateShape(batch=2, n_q_heads=4, n_kv_heads=4, seq_len=70, head_dim=32, dtype=FP32),
+               None, 49, ragged=[9, 33], q_scale=q_scale)
 
 
 def test_attention_generic_paths():
