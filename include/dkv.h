@@ -250,6 +250,7 @@ int dkv_gemm(const void *x, const void *w, float *y, int32_t m, int32_t n, int32
  * DKV_E_UNSUPPORTED if the kernel does not take the shape, DKV_E_INVALID_ARG for unknown option bits. */
 #define DKV_GEMM_OPT_STAGGER    1   /* every workgroup starts its K loop at a different K tile */
 #define DKV_GEMM_OPT_XCD_GROUP  2   /* workgroups that share an XCD's L2 take neighbouring tiles */
+#define DKV_GEMM_OPT_STREAM_W   8   /* weights fetched with the non-temporal hint (dropped with more than one row of tiles) */
 #define DKV_GEMM_OPT_SWIGLU     4   /* fused SwiGLU epilogue: w rows are gate_0, up_0, gate_1, up_1, ...; y is then
                                        a `dtype` (bf16) array [M, N/2] with y[m][j] = silu(x w_{2j}) * (x w_{2j+1});
                                        tile kernels with split_k == 1 only, else DKV_E_UNSUPPORTED */

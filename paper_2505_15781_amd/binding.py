@@ -299,7 +299,7 @@ def concat_reorder(k_cached, v_cached, k_new, v_new, take, dtype):
     return k_out, v_out
 
 
-GEMM_OPT_STAGGER, GEMM_OPT_XCD_GROUP, GEMM_OPT_SWIGLU = 1, 2, 4
+GEMM_OPT_STAGGER, GEMM_OPT_XCD_GROUP, GEMM_OPT_SWIGLU, GEMM_OPT_STREAM_W = 1, 2, 4, 8
 
 
 def gemm(x, w, dtype, kind=None, split_k=1, options=0):

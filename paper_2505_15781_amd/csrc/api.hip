@@ -611,7 +611,7 @@ extern "C" int dkv_gemm_with(const void *x, const void *w, void *yv, int32_t m, 
                              size_t workspace_bytes, void *stream) {
     float *y = static_cast<float *>(yv);
     if (!x || !w || !y || m < 1 || n < 1 || k < 1) { dkv_set_error("bad argument"); return DKV_E_INVALID_ARG; }
-    if (options & ~(DKV_GEMM_OPT_STAGGER | DKV_GEMM_OPT_XCD_GROUP | DKV_GEMM_OPT_SWIGLU)) {
+    if (options & ~(DKV_GEMM_OPT_STAGGER | DKV_GEMM_OPT_XCD_GROUP | DKV_GEMM_OPT_SWIGLU | DKV_GEMM_OPT_STREAM_W)) {
         dkv_set_error("unknown projection option bits 0x%x", options);
         return DKV_E_INVALID_ARG;
     }
@@ -621,7 +621,8 @@ extern "C" int dkv_gemm_with(const void *x, const void *w, void *yv, int32_t m, 
     p.split_k = split_k < 0 ? 2 : split_k;
     p.frac_units = split_k < 0 ? (k / 64) * 3 / 4 : 0;      // split_k = -1 asks for the 3/4 share
     p.flags = ((options & DKV_GEMM_OPT_STAGGER) ? GEMM_FLAG_STAGGER : 0) |
-              ((options & DKV_GEMM_OPT_XCD_GROUP) ? GEMM_FLAG_XCD_GROUP : 0);
+              ((options & DKV_GEMM_OPT_XCD_GROUP) ? GEMM_FLAG_XCD_GROUP : 0) |
+              ((options & DKV_GEMM_OPT_STREAM_W) ? GEMM_FLAG_STREAM_W : 0);
     if (options & DKV_GEMM_OPT_SWIGLU) {
         if (!dkv_gemm_can_fuse_swiglu(dtype, n, k, p)) {
             dkv_set_error("kernel %d with %d K slices cannot fuse SwiGLU (bf16 tile kernels, one K slice, even N)", kind, split_k);
@@ -651,6 +652,7 @@ extern "C" int dkv_gemm(const void *x, const void *w, float *y, int32_t m, int32
     if (m < 1 || n < 1 || k < 1) { dkv_set_error("bad argument"); return DKV_E_INVALID_ARG; }
     GemmPlan p = dkv_gemm_plan(dtype, m, n, k);
     const int options = ((p.flags & GEMM_FLAG_STAGGER) ? DKV_GEMM_OPT_STAGGER : 0) |
-                        ((p.flags & GEMM_FLAG_XCD_GROUP) ? DKV_GEMM_OPT_XCD_GROUP : 0);
+                        ((p.flags & GEMM_FLAG_XCD_GROUP) ? DKV_GEMM_OPT_XCD_GROUP : 0) |
+                        ((p.flags & GEMM_FLAG_STREAM_W) ? DKV_GEMM_OPT_STREAM_W : 0);
     return dkv_gemm_with(x, w, y, m, n, k, dtype, p.kind, p.split_k, options, workspace, workspace_bytes, stream);
 }

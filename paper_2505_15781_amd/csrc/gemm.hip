@@ -31,6 +31,12 @@ typedef __attribute__((address_space(3))) void *lds_ptr_t;
 __device__ __forceinline__ void dma16(const void *g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
 }
+// The same with the non-temporal hint: for weights that no other workgroup will read again (one row of tiles),
+// so that they do not push the activations out of L2. Measured on cold weights: 5-11 % less time for the QKV
+// and gate/up shapes at 16-128 rows; with several rows of tiles the hint costs up to 2x, hence the flag.
+__device__ __forceinline__ void dma16_nt(const void *g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(g), "s"(lds_addr) : "memory", "m0");
+}
 // s_waitcnt immediate: vmcnt(n) [bits 3:0 and 15:14], lgkmcnt(0) when `lgkm0`, expcnt untouched
 __device__ __forceinline__ constexpr int waitcnt_imm(int n, bool lgkm0) {
     return (n & 15) | ((n >> 4) << 14) | 0x0070 | (lgkm0 ? 0 : 0x0F00);
@@ -123,8 +129,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
         const uint32_t base = lds_base + (uint32_t)(stage * STAGE_CHUNKS + wave_u * 64) * 16u;
 #pragma unroll
         for (int i = 0; i < CA; ++i) dma16(pa[i] + koff, base + (uint32_t)(i * NW * 64) * 16u);
+        if (flags & GEMM_FLAG_STREAM_W) {
 #pragma unroll
-        for (int i = 0; i < CW; ++i) dma16(pw[i] + koff, base + (uint32_t)(BM * 8 + i * NW * 64) * 16u);
+            for (int i = 0; i < CW; ++i) dma16_nt(pw[i] + koff, base + (uint32_t)(BM * 8 + i * NW * 64) * 16u);
+        } else {
+#pragma unroll
+            for (int i = 0; i < CW; ++i) dma16(pw[i] + koff, base + (uint32_t)(BM * 8 + i * NW * 64) * 16u);
+        }
     };
 
     f32x16 acc[MT][NT];
@@ -384,6 +395,7 @@ int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, c
         flags = 0;
     }
     if (grid.y < 4) flags &= ~GEMM_FLAG_XCD_GROUP;
+    if (grid.y > 1) flags &= ~GEMM_FLAG_STREAM_W;          // every weight tile is read once per row of tiles
     if ((flags & GEMM_FLAG_SWIGLU) && (grid.z != 1 || (n & 1))) {
         dkv_set_error("the fused SwiGLU epilogue needs one K slice and an even number of columns");
         return DKV_E_INVALID_ARG;
@@ -462,10 +474,12 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
         }
     }
     // Launch options, from the same sweep: a staggered K start pays when one row of tiles sweeps K unsplit or
-    // in two slices (all workgroups would otherwise read the same A columns at once); the XCD-grouped order
+    // in two slices (all workgroups would otherwise read the same A columns at once); weights that are read once
+    // (one row of tiles) are streamed with the non-temporal hint; the XCD-grouped order
     // pays for the largest tiles once there are enough tile rows to form 4-row groups.
     const int tiles_m = ceil_div(m_upper, kKinds[p.kind].bm);
     if (tiles_m == 1 && p.split_k <= 2) p.flags |= GEMM_FLAG_STAGGER;
+    if (tiles_m == 1) p.flags |= GEMM_FLAG_STREAM_W;
     if (((p.kind == GEMM_DMA_256x256 || p.kind == GEMM_DMA_256x192) && tiles_m >= 4) ||
         (p.kind == GEMM_DMA_128x256 && tiles_m >= 6))
         p.flags |= GEMM_FLAG_XCD_GROUP;

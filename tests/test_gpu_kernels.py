@@ -52,7 +52,7 @@ def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
 
 @pytest.mark.parametrize("kind", ["dma_32x128", "dma_64x128", "dma_128x128", "dma_128x256", "dma_256x256",
                                   "dma_128x96", "dma_128x192", "dma_256x192"])
-@pytest.mark.parametrize("options", [1, 2, 3])
+@pytest.mark.parametrize("options", [1, 2, 3, 8, 9])
 @pytest.mark.parametrize("m,n,k,split", [(5, 128, 256, 1), (129, 384, 1024, 1), (300, 520, 768, 2),
                                          (1100, 1536, 512, 1), (1030, 2048, 640, 2)])
 def test_projection_launch_options_leave_the_product_unchanged(kind, options, m, n, k, split):
