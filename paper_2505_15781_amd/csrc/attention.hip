@@ -90,6 +90,13 @@ __device__ __forceinline__ void softmax_step(f32x4 (&st)[NT], float &m_run, floa
     l_run += psum;
 }
 
+// 16 bytes with the non-temporal hint (data that this launch reads once)
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_nt(const void *p) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 #include "attn_shared.h"
 #include "attn_ksplit.h"
 

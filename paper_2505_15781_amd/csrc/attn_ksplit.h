@@ -72,10 +72,19 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
     // chunk i of a lane: key lane / (DH/8) + i * 64 / (DH/8) of the tile, dims [8 (lane % (DH/8)), +8)
     constexpr int ROWS_PER_I = 64 / (DH / 8);
     const int lane_off = (lane / (DH / 8)) * DH + (lane % (DH / 8)) * 8;
+    // One query group per (sequence, kv head): nobody else reads these K/V rows in this launch, so they are
+    // fetched with the non-temporal hint; with several query groups the rows are meant to be found in L2 again.
+    const bool read_once = q_groups == 1;
     auto load_tile = [&](int t) {
         const size_t base = (size_t)t * KT * DH;               // wave-uniform
         const bf16_t *kt = Kb + base + lane_off, *vt = Vb + base + lane_off;
-        if ((t + 1) * KT <= L) {
+        if ((t + 1) * KT <= L && read_once) {
+#pragma unroll
+            for (int i = 0; i < KCH; ++i) {
+                kreg[i] = load16_nt(kt + i * ROWS_PER_I * DH);
+                vreg[i] = load16_nt(vt + i * ROWS_PER_I * DH);
+            }
+        } else if ((t + 1) * KT <= L) {
 #pragma unroll
             for (int i = 0; i < KCH; ++i) {
                 kreg[i] = *reinterpret_cast<const uint4 *>(kt + i * ROWS_PER_I * DH);

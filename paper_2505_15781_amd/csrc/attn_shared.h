@@ -61,13 +61,25 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_shared(
     // per thread: CH chunks (16 B) of K and of V per tile, in register set A or B on their way to LDS
     constexpr int NT = 64 * NW, CH = KT2 * (DH / 8) / NT;
     uint4 kA[CH], vA[CH], kB[CH], vB[CH];
+    // With one block of query tiles per (sequence, kv head) nobody else reads these K/V rows in this launch: they
+    // are fetched with the non-temporal hint; with several blocks they are meant to be found in L2 again.
+    const bool read_once = q_blocks == 1;
     auto load_tile = [&](int t, uint4 (&kr)[CH], uint4 (&vr)[CH]) {
         const int key0 = t * KT2;
+        if (read_once) {
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = key0 + key;
-            kr[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
-            vr[i] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < CH; ++i) {
+                const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = key0 + key;
+                kr[i] = gk < L ? load16_nt(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+                vr[i] = gk < L ? load16_nt(Vb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = key0 + key;
+                kr[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+                vr[i] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+            }
         }
     };
     auto store_tile = [&](int stage, const uint4 (&kr)[CH], const uint4 (&vr)[CH]) {
