@@ -473,12 +473,12 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
             }
         }
     }
-    // Launch options, from the same sweep: a staggered K start pays when one row of tiles sweeps K unsplit or
-    // in two slices (all workgroups would otherwise read the same A columns at once); weights that are read once
+    // Launch options, from the same sweep: a staggered K start pays when there is one row of tiles
+    // (all workgroups of a K slice would otherwise read the same A columns at once); weights that are read once
     // (one row of tiles) are streamed with the non-temporal hint; the XCD-grouped order
     // pays for the largest tiles once there are enough tile rows to form 4-row groups.
     const int tiles_m = ceil_div(m_upper, kKinds[p.kind].bm);
-    if (tiles_m == 1 && p.split_k <= 2) p.flags |= GEMM_FLAG_STAGGER;
+    if (tiles_m == 1) p.flags |= GEMM_FLAG_STAGGER;
     // (not for matrices small enough to stay in the 256 MB last-level cache from one step to the next)
     if (tiles_m == 1 && (size_t)n * k * 2 >= ((size_t)32 << 20)) p.flags |= GEMM_FLAG_STREAM_W;
     if (((p.kind == GEMM_DMA_256x256 || p.kind == GEMM_DMA_256x192) && tiles_m >= 4) ||
