@@ -29,6 +29,18 @@ def test_projection_matches_float64_product(dtype, m, n, k):
     check_close(y, ref, 1e-5, f"gemm {m}x{n}x{k}")
 
 
+@pytest.mark.parametrize("m", [3, 40, 100])
+def test_projection_planned_launch_on_a_weight_matrix_that_is_streamed(m):
+    """A weight matrix of 32 MB: with one row of tiles the planner streams it with the non-temporal hint, slices K
+    and staggers the K start; the product is the same."""
+    import paper_2505_15781_amd as P
+    n, k = 4096, 4096
+    x = D.normal_f32(7, 1, (m, k), bf16=True)
+    w = D.normal_f32(7, 2, (n, k), std=0.02, bf16=True)
+    y = P.gemm(_dev(x, BF16), _dev(w, BF16), BF16).cpu().numpy()
+    check_close(y, x.astype(np.float64) @ w.astype(np.float64).T, 1e-5, f"gemm {m}x{n}x{k}")
+
+
 @pytest.mark.parametrize("kind,split", [("dma_32x128", 1), ("dma_32x128", 3), ("dma_64x128", 2), ("dma_128x128", 1),
                                         ("dma_128x128", 4), ("dma_128x256", 2), ("dma_256x256", 1),
                                         ("dma_256x256", 3), ("dma_128x96", 1), ("dma_128x96", 2),
