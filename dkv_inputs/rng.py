@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 import os
 import numpy as np
 
-_CHUNK_ELEMS = 1 << 24
+_CHUNK_ELEMS = 1 << 20      # draws are keyed per chunk: small enough that every large tensor fills all threads
 
 
 def _gen(seed, stream, chunk=0):

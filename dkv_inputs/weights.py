@@ -20,14 +20,18 @@ _EMBED, _HEAD, _FNORM = 1_000_001, 1_000_002, 1_000_003
 
 
 class SynthWeights:
-    def __init__(self, model, seed, cache_layers=True):
+    def __init__(self, model, seed, cache_layers=True, hold_float64=False):
+        """hold_float64: keep the matrices widened to float64 (same values; a consumer that computes in
+        float64 then does not widen 10^8 entries on every use)."""
         self.model = model
         self.seed = seed
         self._bf16 = model.dtype == BF16
         self._cache = {} if cache_layers else None
+        self._f64 = hold_float64
 
     def _mat(self, stream, shape):
-        return normal_f32(self.seed, stream, shape, std=_STD, bf16=self._bf16)
+        m = normal_f32(self.seed, stream, shape, std=_STD, bf16=self._bf16)
+        return m.astype(np.float64) if self._f64 else m
 
     def _gain(self, stream):
         return normal_f32(self.seed, stream, (self.model.d_model,), std=_GAIN_STD, mean=1.0)

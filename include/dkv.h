@@ -12,8 +12,8 @@
  *    must outlive the context. The library allocates only the small host-side context, and never
  *    device memory.
  *  - All device work is enqueued on the caller's HIP stream (a hipStream_t passed as void*); calls
- *    return without waiting for it, except dkv_init_cache (one-time table upload) and the
- *    dkv_read_* debug calls, which synchronise that stream.
+ *    return without waiting for it, except the dkv_read_* debug calls and dkv_profile_end, which
+ *    synchronise that stream.
  *  - Every call returns 0 on success or a negative DKV_E_* code; dkv_last_error() gives the text
  *    of the most recent failure on this thread. No call aborts or throws.
  *  - Positions are 0-based; the generated region is [prompt_len, prompt_len + gen_len).
@@ -136,10 +136,13 @@ int dkv_init_cache(dkv_ctx **out, const dkv_model_desc *model, const dkv_weights
 /* Compute the active set A_t of step `step` on the device (Eq. 4: everything still masked plus the
  * previous step's commits; all positions, or the generated region, on a refresh; the Greedy set
  * of Sec. 3.4). Rows are ordered sequence by sequence, position ascending.
- * active_idx (dev, nullable) receives the positions [rows]; active_off (dev, nullable) [batch+1]
- * the row offsets of each sequence. host_upper_bound_rows (host, nullable) receives a bound on the
- * row count known from the schedule without reading the device (exact except for Greedy, whose
- * windows may clip or overlap). `step` must be the context's next step, else DKV_E_BAD_STATE.
+ * active_idx (dev, nullable) receives the positions and must have room for batch * seq_len entries:
+ * the call copies as many entries as the schedule's bound below says, which is not known before the
+ * call and can exceed the true row count; entries from active_off[batch] on are undefined.
+ * active_off (dev, nullable) [batch+1] receives the row offsets of each sequence.
+ * host_upper_bound_rows (host, nullable) receives a bound on the row count known from the schedule
+ * without reading the device (exact except for Greedy, whose windows may clip or overlap, and for
+ * shifted logits). `step` must be the context's next step, else DKV_E_BAD_STATE.
  * Calling it is optional: dkv_denoise_step does it when it has not been done for that step. */
 int dkv_select_active(dkv_ctx *ctx, int32_t step, int32_t *active_idx, int32_t *active_off,
                       int32_t *host_upper_bound_rows);
@@ -165,12 +168,24 @@ int dkv_refresh(dkv_ctx *ctx, int32_t scope);
  * dkv_read_rows: active set of the last selected step: positions and offsets [batch+1].
  * dkv_read_candidates: candidates of the last executed step: position, predicted token,
  *   confidence, and offsets [batch+1].
- * dkv_read_hidden: residual stream after the last layer (before the final norm) of the last
- *   executed step, [rows, d_model] fp32. */
+ * dkv_read_hidden: the residual stream of the last executed step, [rows, d_model] fp32, at a layer
+ *   boundary: `layer` = l in [0, n_layers) is the input of block l (l = 0: the embedded rows), `layer` =
+ *   n_layers the output of the last block (before the final norm). The input of block l together with
+ *   the cache rows of layer l is everything one block of Algorithm 1 (lines 3-6) consumes, so a single
+ *   layer can be checked on its own at any step. Only `layer` = n_layers is kept by default; the other
+ *   boundaries are available when dkv_capture_hidden was active during the step, else
+ *   DKV_E_BAD_STATE. */
 int dkv_read_rows(dkv_ctx *ctx, int32_t *pos, int32_t *off, int32_t capacity, int32_t *n_rows);
 int dkv_read_candidates(dkv_ctx *ctx, int32_t *pos, int32_t *tok, float *conf, int32_t *off,
                         int32_t capacity, int32_t *n_cand);
-int dkv_read_hidden(dkv_ctx *ctx, float *out, int32_t capacity_rows, int32_t *n_rows);
+int dkv_read_hidden(dkv_ctx *ctx, int32_t layer, float *out, int32_t capacity_rows, int32_t *n_rows);
+
+/* Debug: from the next step on, every denoising step also copies the residual stream at each layer
+ * boundary into `buffer` (dev), laid out [n_layers + 1][batch * seq_len][d_model] fp32 (slot l = input
+ * of block l, slot n_layers = output of the last block; only the step's rows of each slot are written).
+ * `bytes` is the buffer's size: DKV_E_INVALID_ARG if smaller than that layout. buffer = NULL stops the
+ * copies. The buffer is caller-owned and must stay valid while capturing. */
+int dkv_capture_hidden(dkv_ctx *ctx, float *buffer, size_t bytes);
 
 int dkv_destroy(dkv_ctx *ctx);
 

@@ -66,6 +66,37 @@ class KVStore:
         self.stamp = np.full((batch, seq_len), -1, dtype=np.int32)
 
 
+def layer_forward(model, w, h, pos, off, K_l, V_l):
+    """One pre-norm block on the active rows (Algorithm 1 lines 3-6 for one layer).
+
+    h [R, d] residual stream entering the layer, rows ordered sequence by sequence; pos [R] their
+    sequence positions; off [B+1] row offsets of the sequences; w the layer's weights;
+    K_l, V_l [B][Hkv][L][dh] the layer's position-indexed store, whose rows at the active
+    positions are overwritten with the fresh post-rotation K and V before attending (Eq. 4).
+    Returns the residual stream leaving the layer."""
+    Hq, Hkv, dh = model.n_q_heads, model.n_kv_heads, model.head_dim
+    group = Hq // Hkv
+    B = len(off) - 1
+    a = rmsnorm(h, w["norm1"], model.rms_eps)
+    q = (a @ np.asarray(w["wq"], dtype=np.float64).T).reshape(-1, Hq, dh)
+    k = (a @ np.asarray(w["wk"], dtype=np.float64).T).reshape(-1, Hkv, dh)
+    v = (a @ np.asarray(w["wv"], dtype=np.float64).T).reshape(-1, Hkv, dh)
+    q = rope(q, pos, model.rope_theta)
+    k = rope(k, pos, model.rope_theta)
+    o = np.empty_like(q)
+    for b in range(B):
+        r = slice(off[b], off[b + 1])
+        p = pos[r]
+        K_l[b][:, p, :] = np.transpose(k[r], (1, 0, 2))
+        V_l[b][:, p, :] = np.transpose(v[r], (1, 0, 2))
+        o[r] = attention(q[r], K_l[b], V_l[b], group)
+    h = h + o.reshape(-1, Hq * dh) @ np.asarray(w["wo"], dtype=np.float64).T
+    m = rmsnorm(h, w["norm2"], model.rms_eps)
+    gate = m @ np.asarray(w["w_gate"], dtype=np.float64).T
+    up = m @ np.asarray(w["w_up"], dtype=np.float64).T
+    return h + (silu(gate) * up) @ np.asarray(w["w_down"], dtype=np.float64).T
+
+
 def forward_active(model, weights, tokens, active, store, t, keep_hidden=None):
     """One model call on the active rows.
 
@@ -80,30 +111,10 @@ def forward_active(model, weights, tokens, active, store, t, keep_hidden=None):
     off = np.concatenate([[0], np.cumsum(counts)]).astype(int)
     pos = np.concatenate([np.asarray(a, dtype=np.int64) for a in active]) if off[-1] else np.zeros(0, np.int64)
     seq = np.concatenate([np.full(c, b, dtype=np.int64) for b, c in enumerate(counts)]) if off[-1] else np.zeros(0, np.int64)
-    Hq, Hkv, dh = model.n_q_heads, model.n_kv_heads, model.head_dim
-    group = Hq // Hkv
     embed = weights.embed()
     h = embed[tokens[seq, pos]].astype(np.float64)
     for l in range(model.n_layers):
-        w = weights.layer(l)
-        a = rmsnorm(h, w["norm1"], model.rms_eps)
-        q = (a @ w["wq"].astype(np.float64).T).reshape(-1, Hq, dh)
-        k = (a @ w["wk"].astype(np.float64).T).reshape(-1, Hkv, dh)
-        v = (a @ w["wv"].astype(np.float64).T).reshape(-1, Hkv, dh)
-        q = rope(q, pos, model.rope_theta)
-        k = rope(k, pos, model.rope_theta)
-        o = np.empty_like(q)
-        for b in range(B):
-            r = slice(off[b], off[b + 1])
-            p = pos[r]
-            store.K[l, b][:, p, :] = np.transpose(k[r], (1, 0, 2))
-            store.V[l, b][:, p, :] = np.transpose(v[r], (1, 0, 2))
-            o[r] = attention(q[r], store.K[l, b], store.V[l, b], group)
-        h = h + o.reshape(-1, Hq * dh) @ w["wo"].astype(np.float64).T
-        m = rmsnorm(h, w["norm2"], model.rms_eps)
-        gate = m @ w["w_gate"].astype(np.float64).T
-        up = m @ w["w_up"].astype(np.float64).T
-        h = h + (silu(gate) * up) @ w["w_down"].astype(np.float64).T
+        h = layer_forward(model, weights.layer(l), h, pos, off, store.K[l], store.V[l])
         if keep_hidden is not None:
             keep_hidden.append(h.copy())
     for b in range(B):
@@ -114,7 +125,7 @@ def forward_active(model, weights, tokens, active, store, t, keep_hidden=None):
 def logits_of(model, weights, h_rows):
     """Final norm and vocabulary projection of the given hidden rows: [n, V] float64."""
     a = rmsnorm(h_rows, weights.final_norm(), model.rms_eps)
-    return a @ weights.lm_head().astype(np.float64).T
+    return a @ np.asarray(weights.lm_head(), dtype=np.float64).T
 
 
 def full_forward(model, weights, tokens):

@@ -53,7 +53,8 @@ lib.dkv_denoise_step.argtypes = [c_vp, c_i32, c_vp, c_vp, c_vp]
 lib.dkv_refresh.argtypes = [c_vp, c_i32]
 lib.dkv_read_rows.argtypes = [c_vp, c_vp, c_vp, c_i32, C.POINTER(c_i32)]
 lib.dkv_read_candidates.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, C.POINTER(c_i32)]
-lib.dkv_read_hidden.argtypes = [c_vp, c_vp, c_i32, C.POINTER(c_i32)]
+lib.dkv_read_hidden.argtypes = [c_vp, c_i32, c_vp, c_i32, C.POINTER(c_i32)]
+lib.dkv_capture_hidden.argtypes = [c_vp, c_vp, c_sz]
 lib.dkv_destroy.argtypes = [c_vp]
 
 
@@ -254,12 +255,24 @@ class DkvRun:
                                        off.ctypes.data, cap, C.byref(n)))
         return pos[:n.value].copy(), tok[:n.value].copy(), conf[:n.value].copy(), off
 
-    def read_hidden(self):
+    def read_hidden(self, layer=None):
+        """Residual stream of the last step at a layer boundary (default: after the last block)."""
         cap = self.run.batch * self.run.seq_len
         out = np.empty((cap, self.model.d_model), dtype=np.float32)
         n = c_i32(0)
-        _check(lib.dkv_read_hidden(self.ctx, out.ctypes.data, cap, C.byref(n)))
+        _check(lib.dkv_read_hidden(self.ctx, self.model.n_layers if layer is None else layer, out.ctypes.data,
+                                   cap, C.byref(n)))
         return out[:n.value].copy()
+
+    def capture_hidden(self, on=True):
+        """Keep the residual stream at every layer boundary of the following steps (device buffer held here)."""
+        if on:
+            n = (self.model.n_layers + 1) * self.run.batch * self.run.seq_len * self.model.d_model
+            self._capture = torch.empty(n, dtype=torch.float32, device=self.k_cache.device)
+            _check(lib.dkv_capture_hidden(self.ctx, _ptr(self._capture), n * 4))
+        else:
+            _check(lib.dkv_capture_hidden(self.ctx, None, 0))
+            self._capture = None
 
     def close(self):
         if self.ctx:

@@ -153,6 +153,9 @@ struct dkv_ctx {
     int next_step, selected_step, forced_scope;
     int rows_upper, rows_per_seq_upper, cand_upper;
     int last_rows_upper, last_cand_upper;
+    // optional copies of the residual stream at every layer boundary (debug)
+    float *capture = nullptr;
+    bool last_step_captured = false;
     // optional per-launch timing
     bool prof_on = false;
     struct ProfRec { hipEvent_t a, b; int kind; double bytes, flops; };
@@ -308,19 +311,11 @@ extern "C" int dkv_init_cache(dkv_ctx **out, const dkv_model_desc *model, const 
     c->next_step = 0; c->selected_step = -1; c->forced_scope = -1;
     c->rows_upper = c->cand_upper = c->last_rows_upper = c->last_cand_upper = 0;
 
-    // rotary table in double precision, stored as fp32 (cos, sin) per (position, pair)
-    const int half = model->head_dim / 2;
-    std::vector<float2> tab((size_t)c->L * half);
-    for (int p = 0; p < c->L; ++p)
-        for (int i = 0; i < half; ++i) {
-            double ang = (double)p * pow((double)model->rope_theta, -2.0 * i / model->head_dim);
-            tab[(size_t)p * half + i] = make_float2((float)cos(ang), (float)sin(ang));
-        }
-    hipError_t e = hipMemcpyAsync(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, c->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
-    if (e != hipSuccess) { delete c; dkv_set_error("rotary table upload failed: %s", hipGetErrorString(e)); return DKV_E_HIP; }
-
-    int rc = dkv_launch_init_state(c->stream, buf->tokens, buf->masked, buf->stamp, c->d_prev, c->status,
+    // rotary table (cos, sin) per (position, pair), computed in double precision and stored as fp32
+    int rc = dkv_launch_rope_table(c->stream, reinterpret_cast<float *>(c->rope), c->L, model->head_dim,
+                                   (double)model->rope_theta);
+    if (rc) { delete c; return rc; }
+    rc = dkv_launch_init_state(c->stream, buf->tokens, buf->masked, buf->stamp, c->d_prev, c->status,
                                    run->batch, c->L, run->prompt_len, c->k, model->mask_id);
     const size_t nlog = (size_t)run->steps * run->batch * c->k;
     if (!rc) rc = dkv_launch_fill_i32(c->stream, buf->decoded_pos, -1, nlog);
@@ -342,7 +337,7 @@ extern "C" int dkv_select_active(dkv_ctx *c, int32_t step, int32_t *active_idx, 
         int rc = do_select(c, step);
         if (rc) return rc;
     }
-    if (active_idx)
+    if (active_idx)   // the schedule's bound of entries; those past the true count are stale
         DKV_HIP_TRY(hipMemcpyAsync(active_idx, c->row_pos, (size_t)c->rows_upper * 4, hipMemcpyDeviceToDevice, c->stream));
     if (active_off)
         DKV_HIP_TRY(hipMemcpyAsync(active_off, c->row_off, (size_t)(c->r.batch + 1) * 4, hipMemcpyDeviceToDevice, c->stream));
@@ -380,7 +375,15 @@ extern "C" int dkv_denoise_step(dkv_ctx *c, int32_t step, const int32_t *forced_
     if ((rc = dkv_launch_embed_norm(dt, s, rows, d, c->embed, c->buf.tokens, c->row_pos, c->row_seq, c->counts,
                                     c->n1[0], c->h, c->a, c->buf.stamp, c->L, m.rms_eps, step))) return rc;
     const AttnPlan ap = dkv_attn_plan(dt, r.batch, m.n_q_heads, m.n_kv_heads, c->L, m.head_dim, c->rows_per_seq_upper);
+    const size_t slot_floats = (size_t)c->lay.rows_cap * d;
+    auto capture = [&](int slot) -> int {
+        if (!c->capture || rows <= 0) return DKV_OK;
+        DKV_HIP_TRY(hipMemcpyAsync(c->capture + slot * slot_floats, c->h, (size_t)rows * d * 4,
+                                   hipMemcpyDeviceToDevice, s));
+        return DKV_OK;
+    };
     for (int l = 0; l < m.n_layers; ++l) {
+        if ((rc = capture(l))) return rc;
         char *Kl = static_cast<char *>(c->buf.k_cache) + layer_elems * c->es * l;
         char *Vl = static_cast<char *>(c->buf.v_cache) + layer_elems * c->es * l;
         GemmPlan p = dkv_gemm_plan(dt, rows, nqkv, d);
@@ -415,6 +418,8 @@ extern "C" int dkv_denoise_step(dkv_ctx *c, int32_t step, const int32_t *forced_
         if ((rc = dkv_launch_residual_norm(dt, s, rows, d, c->part, p.split_k, (size_t)rows * d, c->counts, next_gain,
                                            c->h, c->a, m.rms_eps))) return rc;
     }
+    if ((rc = capture(m.n_layers))) return rc;
+    c->last_step_captured = c->capture != nullptr;
     // vocabulary head on the candidate rows only (same result as projecting every active row)
     if ((rc = dkv_launch_gather_rows(dt, s, cands, c->a, c->cand_row, c->counts, c->a_c, d))) return rc;
     float *lg = logits_out ? logits_out : c->logits;
@@ -491,17 +496,31 @@ extern "C" int dkv_read_candidates(dkv_ctx *c, int32_t *pos, int32_t *tok, float
     return DKV_OK;
 }
 
-extern "C" int dkv_read_hidden(dkv_ctx *c, float *out, int32_t capacity_rows, int32_t *n_rows) {
+extern "C" int dkv_read_hidden(dkv_ctx *c, int32_t layer, float *out, int32_t capacity_rows, int32_t *n_rows) {
     if (!c || !out || !n_rows) { dkv_set_error("null argument"); return DKV_E_INVALID_ARG; }
+    if (layer < 0 || layer > c->m.n_layers) { dkv_set_error("layer boundary %d outside 0..%d", layer, c->m.n_layers); return DKV_E_INVALID_ARG; }
     if (c->next_step == 0) { dkv_set_error("no step has been executed yet"); return DKV_E_BAD_STATE; }
+    if (layer != c->m.n_layers && !c->last_step_captured) {
+        dkv_set_error("layer boundary %d was not kept: dkv_capture_hidden was not active during the last step", layer);
+        return DKV_E_BAD_STATE;
+    }
     int n = 0;
     DKV_HIP_TRY(hipMemcpyAsync(&n, c->counts, 4, hipMemcpyDeviceToHost, c->stream));
     DKV_HIP_TRY(hipStreamSynchronize(c->stream));
     if (n > capacity_rows) { dkv_set_error("%d rows do not fit capacity %d", n, capacity_rows); return DKV_E_INVALID_ARG; }
     if (n > c->last_rows_upper) { dkv_set_error("%d rows exceed the schedule's bound %d", n, c->last_rows_upper); return DKV_E_BAD_STATE; }
-    DKV_HIP_TRY(hipMemcpyAsync(out, c->h, (size_t)n * c->m.d_model * 4, hipMemcpyDeviceToHost, c->stream));
+    const float *src = layer == c->m.n_layers ? c->h : c->capture + (size_t)layer * c->lay.rows_cap * c->m.d_model;
+    DKV_HIP_TRY(hipMemcpyAsync(out, src, (size_t)n * c->m.d_model * 4, hipMemcpyDeviceToHost, c->stream));
     DKV_HIP_TRY(hipStreamSynchronize(c->stream));
     *n_rows = n;
+    return DKV_OK;
+}
+
+extern "C" int dkv_capture_hidden(dkv_ctx *c, float *buffer, size_t bytes) {
+    if (!c) { dkv_set_error("null context"); return DKV_E_INVALID_ARG; }
+    const size_t need = (size_t)(c->m.n_layers + 1) * c->lay.rows_cap * c->m.d_model * sizeof(float);
+    if (buffer && bytes < need) { dkv_set_error("capture buffer has %zu bytes, %zu needed", bytes, need); return DKV_E_INVALID_ARG; }
+    c->capture = buffer;
     return DKV_OK;
 }
 
@@ -553,11 +572,12 @@ extern "C" size_t dkv_attn_update_workspace_bytes(int32_t batch, int32_t n_q_hea
     return align_up(dkv_attn_partial_bytes(p, batch, n_q_heads, n_kv_heads, head_dim) + 256, 256);
 }
 
-extern "C" int dkv_attn_update(void *k_cache, void *v_cache, const void *q, const void *k_new, const void *v_new,
-                               const int32_t *active_idx, const int32_t *active_off, void *out, int32_t rows,
-                               int32_t max_rows_per_seq, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
-                               int32_t seq_len, int32_t head_dim, int32_t dtype, void *workspace,
-                               size_t workspace_bytes, void *stream) {
+namespace {
+int attn_update_impl(void *k_cache, void *v_cache, const void *q, const void *k_new, const void *v_new,
+                     const int32_t *active_idx, const int32_t *active_off, void *out, int32_t rows,
+                     int32_t max_rows_per_seq, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                     int32_t seq_len, int32_t head_dim, int32_t dtype, void *workspace, size_t workspace_bytes,
+                     const char *workspace_name, void *stream) {
     if (!k_cache || !v_cache || !active_off) { dkv_set_error("null argument"); return DKV_E_INVALID_ARG; }
     if (rows < 0 || batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || seq_len < 1 ||
         max_rows_per_seq < 0 || max_rows_per_seq > seq_len || rows > (long)batch * max_rows_per_seq) {
@@ -570,7 +590,7 @@ extern "C" int dkv_attn_update(void *k_cache, void *v_cache, const void *q, cons
     AttnPlan p = dkv_attn_plan(dtype, batch, n_q_heads, n_kv_heads, seq_len, head_dim, max_rows_per_seq);
     size_t need = dkv_attn_partial_bytes(p, batch, n_q_heads, n_kv_heads, head_dim);
     if (need > workspace_bytes || (need && !workspace)) {
-        dkv_set_error("workspace has %zu bytes, %zu needed", workspace_bytes, need);
+        dkv_set_error("%s has %zu bytes, %zu needed", workspace_name, workspace_bytes, need);
         return DKV_E_WORKSPACE_TOO_SMALL;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -583,6 +603,17 @@ extern "C" int dkv_attn_update(void *k_cache, void *v_cache, const void *q, cons
     if (rc) return rc;
     return dkv_launch_attention(dtype, q, k_cache, v_cache, active_off, out, batch, n_q_heads, n_kv_heads, seq_len,
                                 head_dim, rows, p, workspace, AttnFusedUpdate{nullptr, nullptr, nullptr}, s);
+}
+}  // namespace
+
+extern "C" int dkv_attn_update(void *k_cache, void *v_cache, const void *q, const void *k_new, const void *v_new,
+                               const int32_t *active_idx, const int32_t *active_off, void *out, int32_t rows,
+                               int32_t max_rows_per_seq, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                               int32_t seq_len, int32_t head_dim, int32_t dtype, void *workspace,
+                               size_t workspace_bytes, void *stream) {
+    return attn_update_impl(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, rows, max_rows_per_seq,
+                            batch, n_q_heads, n_kv_heads, seq_len, head_dim, dtype, workspace, workspace_bytes,
+                            "workspace", stream);
 }
 
 extern "C" int dkv_concat_reorder(const void *k_cached, const void *v_cached, const void *k_new, const void *v_new,

@@ -13,6 +13,8 @@
 //
 // generic kernel (fp32 mode and odd head sizes): one wavefront per (row, query head), lanes stride
 // over the keys, fp32 FMA, exact expf.
+#include <atomic>
+
 #include "common.h"
 
 namespace {
@@ -291,12 +293,12 @@ int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache,
         const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_groups * plan.splits);
 #define KSPLIT_F(D, NQ, NW, F)                                                                                 \
     do {                                                                                                       \
-        static bool lds_ok = false;                                                                            \
+        static std::atomic<bool> lds_ok{false};    /* idempotent call: racing threads only repeat it */       \
         const size_t smem = NW * AttnSmem<D>::WAVE_BYTES;                                                      \
-        if (!lds_ok) {                                                                                         \
+        if (!lds_ok.load(std::memory_order_acquire)) {                                                         \
             DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_ksplit<D, NQ, NW, F>),   \
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));           \
-            lds_ok = true;                                                                                     \
+            lds_ok.store(true, std::memory_order_release);                                                     \
         }                                                                                                      \
         hipLaunchKernelGGL((attn_bf16_ksplit<D, NQ, NW, F>), dim3(wgs), dim3(64 * NW), smem, stream,           \
                            (const bf16_t *)q, (bf16_t *)k_cache, (bf16_t *)v_cache, row_off, (bf16_t *)out,    \
@@ -343,13 +345,13 @@ int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache,
     } else if (plan.shared_nq) {
         const size_t smem = 2 * 64 * ((128 * 2 + 16) + (128 * 2 + 32));   // two stages of 64 K rows and 64 V rows
         const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_blocks * plan.splits);
-        static bool lds_ok = false;
-        if (!lds_ok) {
+        static std::atomic<bool> lds_ok{false};
+        if (!lds_ok.load(std::memory_order_acquire)) {
             DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2, 4>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
             DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1, 8>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-            lds_ok = true;
+            lds_ok.store(true, std::memory_order_release);
         }
 #define SHARED(NQ_, NW_)                                                                                          \
     hipLaunchKernelGGL((attn_bf16_shared<NQ_, NW_>), dim3(wgs), dim3(64 * NW_), smem, stream, (const bf16_t *)q,  \

@@ -18,6 +18,8 @@
 // together on one XCD (hardware sends workgroup i to XCD i mod 8) cover a compact 4 x 8 block of tiles and
 // share their A and W tiles through that XCD's L2 (hit rate 54 % -> 78 % and 5 % less time at 6144 rows).
 // bf16, other K (multiple of 8): `gemm_reg`, register-staged tiles. fp32 mode / anything else: `gemm_simt`.
+#include <atomic>
+
 #include "common.h"
 
 namespace {
@@ -378,11 +380,12 @@ int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, c
                int split, int frac_units, int flags, hipStream_t s) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
     constexpr int smem = STAGES * (BM + BN) * 128;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // set once per process; the call is idempotent, so threads that race here only repeat it
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_dma<MT, NT, WM, WN, STAGES>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int kt_total = k / BK, kps = ceil_div(kt_total, split);
     dim3 grid(ceil_div(n, BN), ceil_div(m_upper, BM), ceil_div(kt_total, kps));

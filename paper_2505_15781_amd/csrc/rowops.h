@@ -57,6 +57,8 @@ int dkv_launch_head_stats(hipStream_t s, int cands, const float *logits, const i
 int dkv_launch_commit(const CommitArgs &a, hipStream_t s);
 int dkv_launch_init_state(hipStream_t s, int *tokens, uint8_t *masked, int *stamp, int *d_prev, int *status,
                           int batch, int L, int P, int k, int mask_id);
+// table[p][i] = (cos, sin)(p * theta^(-2 i / dh)), i < dh / 2, evaluated in double precision
+int dkv_launch_rope_table(hipStream_t s, float *table, int L, int dh, double theta);
 int dkv_launch_fill_i32(hipStream_t s, int *p, int v, size_t n);
 int dkv_launch_fill_u8(hipStream_t s, uint8_t *p, uint8_t v, size_t n);
 int dkv_launch_concat_reorder(hipStream_t s, const void *k_cached, const void *v_cached, const void *k_new,

@@ -454,6 +454,15 @@ __global__ void init_state_kernel(int *tokens, uint8_t *masked, int *stamp, int 
     if (i == 0) *status = 0;
 }
 
+// Rotary angles of every (position, pair): the rotation follows the token's true position (Appendix A).
+__global__ void rope_table_kernel(float2 *table, int L, int half, double theta) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)L * half) return;
+    const int p = (int)(i / half), j = (int)(i % half);
+    const double ang = (double)p * pow(theta, -(double)j / (double)half);
+    table[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
 __global__ void fill_i32_kernel(int *p, int v, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -663,6 +672,15 @@ int dkv_launch_init_state(hipStream_t s, int *tokens, uint8_t *masked, int *stam
     if ((size_t)batch * k > n) n = (size_t)batch * k;
     hipLaunchKernelGGL(init_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, tokens, masked,
                        stamp, d_prev, status, batch, L, P, k, mask_id);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_rope_table(hipStream_t s, float *table, int L, int dh, double theta) {
+    const size_t n = (size_t)L * (dh / 2);
+    if (!n) return DKV_OK;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<float2 *>(table), L, dh / 2, theta);
     DKV_LAUNCH_CHECK();
     return DKV_OK;
 }
