@@ -239,6 +239,22 @@ int dkv_attn_update(void *k_cache, void *v_cache, const void *q, const void *k_n
                     int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim,
                     int32_t dtype, void *workspace, size_t workspace_bytes, void *stream);
 
+/* dkv_attn_update for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, same kernels and the same
+ * result as dkv_attn_update, but the scratch of key-sliced attention (partial softmax records) is a
+ * DKV_STATIC_SCRATCH_BYTES array inside the library's device image; the call allocates nothing. Shapes whose
+ * scratch (dkv_attn_update_workspace_bytes) exceeds that size get DKV_E_WORKSPACE_TOO_SMALL and nothing is
+ * launched. Each GPU holds one such array for the life of the process and all calls on that GPU share it:
+ * calls that overlap on one GPU (different streams or threads) race on it; calls on one stream are ordered.
+ * Nothing in the array needs clearing between calls. The first call on a device looks the array up and must
+ * not happen inside a graph capture. */
+#define DKV_STATIC_SCRATCH_BYTES (4u << 20)
+int dkv_attn_update_static(void *k_cache, void *v_cache, const void *q, const void *k_new,
+                           const void *v_new, const int32_t *active_idx, const int32_t *active_off,
+                           void *out, int32_t rows, int32_t max_rows_per_seq, int32_t batch,
+                           int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim,
+                           int32_t dtype, void *stream);
+
 /* The paper's own cache operator, concat_reorder (Appendix A; Algorithm 1 lines 4-5), on its compact
  * layout: per (sequence, kv head) the n_cached cached rows and the n_new freshly computed rows are
  * concatenated and row i of the result is row take[b][i] of that concatenation (the order that puts the next

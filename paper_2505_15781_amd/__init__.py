@@ -3,7 +3,7 @@
 The binding (and with it libdkv.so) is loaded on first use of one of the names below, so that
 `python -m paper_2505_15781_amd.build` can (re)build the library when none, or a stale one, is there.
 """
-_BINDING_NAMES = ("lib", "DkvError", "DkvRun", "attn_update", "attn_update_workspace_bytes",
+_BINDING_NAMES = ("lib", "DkvError", "DkvRun", "attn_update", "attn_update_static", "attn_update_workspace_bytes",
                   "gemm", "GEMM_KINDS", "concat_reorder", "BF16", "FP32", "last_error")
 
 

@@ -73,6 +73,8 @@ lib.dkv_profile_end.argtypes = [c_vp, C.POINTER(ProfEntry)]
 lib.dkv_attn_update_workspace_bytes.restype = c_sz
 lib.dkv_attn_update_workspace_bytes.argtypes = [c_i32] * 7
 lib.dkv_attn_update.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp, c_sz, c_vp]
+lib.dkv_attn_update_static.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp]
+STATIC_SCRATCH_BYTES = 4 << 20
 lib.dkv_concat_reorder.argtypes = [c_vp] * 7 + [c_i32] * 6 + [c_vp]
 lib.dkv_gemm_workspace_bytes.restype = c_sz
 lib.dkv_gemm_workspace_bytes.argtypes = [c_i32] * 4
@@ -299,6 +301,16 @@ def attn_update(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, 
                                _ptr(active_off), _ptr(out), rows, max_rows_per_seq, B, Hq, Hkv, L, dh, dtype,
                                _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
                                _stream()))
+
+
+def attn_update_static(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, rows, max_rows_per_seq,
+                       dtype):
+    """dkv_attn_update without a workspace argument: the library's static scratch array is used."""
+    B, Hkv, L, dh = k_cache.shape
+    Hq = q.shape[1] if q is not None and q.dim() == 3 else out.shape[1]
+    _check(lib.dkv_attn_update_static(_ptr(k_cache), _ptr(v_cache), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                      _ptr(active_idx), _ptr(active_off), _ptr(out), rows, max_rows_per_seq, B, Hq,
+                                      Hkv, L, dh, dtype, _stream()))
 
 
 def concat_reorder(k_cached, v_cached, k_new, v_new, take, dtype):

@@ -3,6 +3,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -614,6 +615,48 @@ extern "C" int dkv_attn_update(void *k_cache, void *v_cache, const void *q, cons
     return attn_update_impl(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, rows, max_rows_per_seq,
                             batch, n_q_heads, n_kv_heads, seq_len, head_dim, dtype, workspace, workspace_bytes,
                             "workspace", stream);
+}
+
+// ---- the same operation for callers that cannot allocate ------------------------------------------------
+// The partial (max, sum, output) records of key-sliced attention live in a device array that is part of the
+// library's image: every GPU the library runs on holds its own copy for the life of the process.
+static __device__ __align__(256) unsigned char scratch[DKV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};        // device address of `scratch` on each device, looked up once
+
+// Device address of this GPU's copy of `scratch` (the array's name is only a host-side handle).
+int static_scratch(void **ptr) {
+    int dev = -1;
+    DKV_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { dkv_set_error("device ordinal %d not supported", dev); return DKV_E_UNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        DKV_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { dkv_set_error("hipGetSymbolAddress returned a null address"); return DKV_E_HIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return DKV_OK;
+}
+}  // namespace
+
+extern "C" int dkv_attn_update_static(void *k_cache, void *v_cache, const void *q, const void *k_new,
+                                      const void *v_new, const int32_t *active_idx, const int32_t *active_off,
+                                      void *out, int32_t rows, int32_t max_rows_per_seq, int32_t batch,
+                                      int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim,
+                                      int32_t dtype, void *stream) {
+    void *ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc) return rc;
+    // Every record the merge kernel reads is written by the attention kernel of the same call, so nothing in
+    // the array has to start at zero; contents left by an earlier (larger) call are never read.
+    return attn_update_impl(k_cache, v_cache, q, k_new, v_new, active_idx, active_off, out, rows, max_rows_per_seq,
+                            batch, n_q_heads, n_kv_heads, seq_len, head_dim, dtype, ws, DKV_STATIC_SCRATCH_BYTES,
+                            "the library's static scratch array", stream);
 }
 
 extern "C" int dkv_concat_reorder(const void *k_cached, const void *v_cached, const void *k_new, const void *v_new,
