@@ -194,7 +194,9 @@ int dkv_destroy(dkv_ctx *ctx);
  * the context's stream. dkv_profile_end synchronises the stream and fills `out` (host, array of
  * DKV_PROF_KINDS entries) with, per kernel kind: number of launches, summed duration in
  * milliseconds, and summed algorithmic bytes and flops of those launches:
- *   projection  bytes = (M*K + N*K) * sizeof(element) + 4*M*N   flops = 2*M*N*K
+ *   projection  bytes = (M*K + N*K) * sizeof(element) + output bytes   flops = 2*M*N*K
+ *               (output: 4*M*N; M*(N/2)*sizeof(element) for gate/up with the fused SwiGLU; 0 for the
+ *               vocabulary projection, whose epilogue keeps the softmax statistics only)
  *   attention   bytes = (2*batch*n_kv_heads*seq_len + 2*rows*n_q_heads) * head_dim * sizeof(element)
  *               flops = 4*rows*n_q_heads*seq_len*head_dim
  * with M the schedule's row count of the step. Kinds: */

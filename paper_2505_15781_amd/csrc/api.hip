@@ -57,6 +57,8 @@ struct Layout {
     size_t head_part;
     size_t part_floats, attn_part_bytes;
     int rows_cap, cand_cap;
+    int head_tiles_cap;    // most column tiles of the vocabulary projection
+    bool head_fused;       // softmax statistics leave the vocabulary projection's epilogue: no fp32 logits buffer
 };
 
 Layout make_layout(const dkv_model_desc &m, const dkv_run_desc &r) {
@@ -81,12 +83,17 @@ Layout make_layout(const dkv_model_desc &m, const dkv_run_desc &r) {
         if (c > pf) pf = c;
         if (d > pf) pf = d;
     }
+    y.head_fused = true;
+    y.head_tiles_cap = 1;
     for (int c = 1; c <= y.cand_cap; ++c) {
         GemmPlan p = dkv_gemm_plan(m.dtype, c, m.vocab, m.d_model);
         if (p.split_k > 1) {
             size_t a = (size_t)p.split_k * c * m.vocab;
             if (a > pf) pf = a;
         }
+        // the epilogue needs the tile kernel with one K slice for every candidate count of the run
+        if (!dkv_gemm_can_fuse_head(m.dtype, m.d_model, p)) y.head_fused = false;
+        else if (dkv_gemm_tiles_n(p, m.vocab) > y.head_tiles_cap) y.head_tiles_cap = dkv_gemm_tiles_n(p, m.vocab);
     }
     y.part_floats = pf;
     size_t ap = 0;
@@ -122,8 +129,11 @@ Layout make_layout(const dkv_model_desc &m, const dkv_run_desc &r) {
     y.attn_out = take((size_t)y.rows_cap * qn * es);
     y.f = take((size_t)y.rows_cap * m.d_ffn * es);
     y.a_c = take((size_t)y.cand_cap * m.d_model * es);
-    y.logits = take((size_t)y.cand_cap * m.vocab * 4);
-    y.head_part = take(dkv_head_stats_scratch_bytes(y.cand_cap));
+    // fp32 logits of the candidate rows: only when the head's statistics cannot leave the projection's epilogue
+    // (a caller who wants the logits passes a buffer of their own)
+    y.logits = take(y.head_fused ? 0 : (size_t)y.cand_cap * m.vocab * 4);
+    y.head_part = take(y.head_fused ? (size_t)y.cand_cap * y.head_tiles_cap * sizeof(HeadPartial)
+                                    : dkv_head_stats_scratch_bytes(y.cand_cap));
     y.part = take(y.part_floats * 4);
     y.attn_part = take(y.attn_part_bytes);
     y.total = o;
@@ -188,7 +198,9 @@ template <typename F> int timed(dkv_ctx *c, int kind, double bytes, double flops
 int timed_gemm(dkv_ctx *c, const void *A, const void *W, float *out, int m, const int *m_dev, int n, int k,
                GemmPlan p) {
     const double es = (double)c->es;
-    return timed(c, p.kind, ((double)m * k + (double)n * k) * es + 4.0 * m * n,
+    // output bytes: fp32 [M, N], or the fused SwiGLU's [M, N/2] elements
+    const double out_bytes = (p.flags & GEMM_FLAG_SWIGLU) ? es * m * (n / 2) : 4.0 * m * n;
+    return timed(c, p.kind, ((double)m * k + (double)n * k) * es + out_bytes,
                  2.0 * m * n * k,
                  [&] { return dkv_launch_gemm(c->m.dtype, A, W, out, m, m, m_dev, n, k, p, c->stream); });
 }
@@ -423,16 +435,33 @@ extern "C" int dkv_denoise_step(dkv_ctx *c, int32_t step, const int32_t *forced_
     c->last_step_captured = c->capture != nullptr;
     // vocabulary head on the candidate rows only (same result as projecting every active row)
     if ((rc = dkv_launch_gather_rows(dt, s, cands, c->a, c->cand_row, c->counts, c->a_c, d))) return rc;
-    float *lg = logits_out ? logits_out : c->logits;
     GemmPlan hp = dkv_gemm_plan(dt, cands, m.vocab, d);
-    if (hp.split_k == 1) {
-        if ((rc = timed_gemm(c, c->a_c, c->lm_head, lg, cands, n_cand, m.vocab, d, hp))) return rc;
+    if (c->lay.head_fused) {
+        // softmax maximum, sum and arg max per column tile leave the projection's epilogue and a small kernel merges
+        // the tiles of a row: the [candidates, vocab] logits are never written (unless the caller asks for them)
+        GemmEpilogue eh;
+        eh.kind = EPI_HEAD;
+        eh.out = logits_out;
+        eh.head_part = static_cast<HeadPartial *>(c->head_part);
+        eh.head_tiles = dkv_gemm_tiles_n(hp, m.vocab);
+        eh.mask_id = m.mask_id;
+        eh.status = c->status;
+        rc = timed(c, hp.kind, ((double)cands * d + (double)m.vocab * d) * (double)c->es + (logits_out ? 4.0 * cands * m.vocab : 0.0),
+                   2.0 * cands * m.vocab * d,
+                   [&] { return dkv_launch_gemm_head(c->a_c, c->lm_head, cands, n_cand, m.vocab, d, hp, eh, s); });
+        if (rc) return rc;
+        if ((rc = dkv_launch_head_merge(s, cands, c->head_part, eh.head_tiles, c->counts, c->cand_tok, c->cand_conf, c->status))) return rc;
     } else {
-        if ((rc = timed_gemm(c, c->a_c, c->lm_head, c->part, cands, n_cand, m.vocab, d, hp))) return rc;
-        if ((rc = dkv_launch_reduce_partials(s, c->part, hp.split_k, (size_t)cands * m.vocab, lg, (size_t)cands * m.vocab))) return rc;
+        float *lg = logits_out ? logits_out : c->logits;
+        if (hp.split_k == 1) {
+            if ((rc = timed_gemm(c, c->a_c, c->lm_head, lg, cands, n_cand, m.vocab, d, hp))) return rc;
+        } else {
+            if ((rc = timed_gemm(c, c->a_c, c->lm_head, c->part, cands, n_cand, m.vocab, d, hp))) return rc;
+            if ((rc = dkv_launch_reduce_partials(s, c->part, hp.split_k, (size_t)cands * m.vocab, lg, (size_t)cands * m.vocab))) return rc;
+        }
+        if ((rc = dkv_launch_head_stats(s, cands, lg, c->counts, m.vocab, m.mask_id, c->cand_tok, c->cand_conf, c->status,
+                                        c->head_part))) return rc;
     }
-    if ((rc = dkv_launch_head_stats(s, cands, lg, c->counts, m.vocab, m.mask_id, c->cand_tok, c->cand_conf, c->status,
-                                    c->head_part))) return rc;
 
     CommitArgs ca;
     ca.cand_off = c->cand_off; ca.cand_pos = c->cand_pos; ca.cand_tok = c->cand_tok; ca.cand_conf = c->cand_conf;

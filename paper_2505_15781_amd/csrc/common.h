@@ -85,6 +85,45 @@ struct GemmPlan {
 GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k);
 int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p);
 
+// Per (candidate row, vocabulary range): running maximum of the logits, sum of exp(x - max) over the range,
+// index of the maximum (lowest on ties), and whether a NaN was seen.
+struct HeadPartial {
+    float max, sum;
+    int idx, nan;
+};
+
+// What a projection launch (gemm_dma kinds) does with its finished tile. Only epilogues that do not have to load
+// anything are fused: measured on MI355X, an epilogue that reads (residual rows, rotary angles, parked K slices) runs
+// at the tail of a workgroup that has its compute unit to itself, nothing hides the latency of its loads, and it costs
+// as much as, or more than, the row kernel it would replace.
+enum {
+    EPI_STORE = 0,   // partial[slice][m][n] = product of the K slice (fp32)
+    EPI_SWIGLU,      // out[m][n/2] = silu(gate) * up (bf16); W rows interleave gate_j, up_j; one K slice
+    EPI_HEAD         // vocabulary head: per row and column tile (max, sum exp, arg max) with MASK excluded; one K slice
+};
+struct GemmEpilogue {
+    int kind = EPI_STORE;
+    void *out = nullptr;              // EPI_SWIGLU: bf16 [m][N/2]; EPI_HEAD: fp32 logits [m][N] or null (not written)
+    HeadPartial *head_part = nullptr; // EPI_HEAD: [m][head_tiles]
+    int head_tiles = 0, mask_id = -1;
+    int *status = nullptr;            // EPI_HEAD: STATUS_NAN is raised here
+};
+// Column tiles of a plan's kernel for N columns (the second dimension of head_part).
+int dkv_gemm_tiles_n(const GemmPlan &plan, int n);
+// The vocabulary projection with the softmax statistics in its epilogue (gemm_dma kinds, one K slice).
+bool dkv_gemm_can_fuse_head(int dtype, int k, const GemmPlan &plan);
+int dkv_launch_gemm_head(const void *A, const void *W, int m_upper, const int *m_dev, int n, int k, GemmPlan plan,
+                         const GemmEpilogue &ep, hipStream_t stream);
+
+// one translation unit per epilogue holds the tile kernels instantiated with it
+#define DKV_DECLARE_DISPATCH(name)                                                                                   \
+    int dkv_dispatch_dma_##name(const void *A, const void *W, float *partial, int m_upper, int m_cap, const int *m_dev, \
+                                int n, int k, const GemmPlan &plan, const GemmEpilogue &ep, hipStream_t stream);
+DKV_DECLARE_DISPATCH(store)
+DKV_DECLARE_DISPATCH(swiglu)
+DKV_DECLARE_DISPATCH(head)
+#undef DKV_DECLARE_DISPATCH
+
 // partial[s][m][n] (fp32, stride m_cap rows per slice) = A[m, k-slice] * W[n, k-slice]^T.
 // Rows >= *m_dev (when m_dev != nullptr) are neither read nor written.
 // With GEMM_FLAG_SWIGLU in plan.flags (gemm_dma kinds, one K slice, W rows interleaved gate_j, up_j): `partial` is

@@ -54,6 +54,9 @@ constexpr int HEAD_SLICES = 16;     // vocabulary ranges per candidate row in th
 size_t dkv_head_stats_scratch_bytes(int cands);
 int dkv_launch_head_stats(hipStream_t s, int cands, const float *logits, const int *counts, int V,
                           int mask_id, int *tok, float *conf, int *status, void *scratch);
+// merge of the per-column-tile records that the vocabulary projection's epilogue leaves: [cands][n_part]
+int dkv_launch_head_merge(hipStream_t s, int cands, const void *head_part, int n_part, const int *counts, int *tok,
+                          float *conf, int *status);
 int dkv_launch_commit(const CommitArgs &a, hipStream_t s);
 int dkv_launch_init_state(hipStream_t s, int *tokens, uint8_t *masked, int *stamp, int *d_prev, int *status,
                           int batch, int L, int P, int k, int mask_id);

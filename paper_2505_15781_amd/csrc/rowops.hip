@@ -287,11 +287,6 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
 // Two kernels: the vocabulary is cut into HEAD_SLICES ranges so that a handful of candidate rows still
 // occupies the chip; every (row, range) block makes one pass keeping a running (max, sum of exp, arg max),
 // the second kernel merges the ranges of a row.
-struct HeadPartial {
-    float max, sum;     // sum of exp(x - max) over the range
-    int idx, nan;
-};
-
 __device__ __forceinline__ void head_merge(float &m, float &s, int &i, float om, float os, int oi) {
     if (om > m || (om == m && oi < i)) {
         s = s * expf(m - om) + os;       // m == -inf only with s == 0: exp(-inf) * 0 is never formed as inf * 0
@@ -356,22 +351,29 @@ __global__ __launch_bounds__(256) void head_stats_partial_kernel(const float *__
     }
 }
 
-__global__ __launch_bounds__(64) void head_stats_final_kernel(const HeadPartial *__restrict__ part,
-                                                              const int *__restrict__ counts,
-                                                              int *__restrict__ tok, float *__restrict__ conf,
-                                                              int *__restrict__ status) {
-    const int c = blockIdx.x * 64 + threadIdx.x;
+__global__ __launch_bounds__(256) void head_stats_final_kernel(const HeadPartial *__restrict__ part, int n_part,
+                                                               const int *__restrict__ counts,
+                                                               int *__restrict__ tok, float *__restrict__ conf,
+                                                               int *__restrict__ status) {
+    // one wavefront per candidate row; the merge keeps the lower token id on equal maxima in any order
+    const int lane = threadIdx.x & 63;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (c >= counts[1]) return;
     float m = -INFINITY, sum = 0.f;
     int bi = 0x7fffffff, nan = 0;
-    for (int s = 0; s < HEAD_SLICES; ++s) {             // ascending ranges: ties go to the lower token id
-        const HeadPartial p = part[(size_t)c * HEAD_SLICES + s];
+    for (int s = lane; s < n_part; s += 64) {
+        const HeadPartial p = part[(size_t)c * n_part + s];
         head_merge(m, sum, bi, p.max, p.sum, p.idx);
         nan |= p.nan;
     }
-    if (nan) atomicOr(status, STATUS_NAN);
-    tok[c] = bi;
-    conf[c] = 1.0f / sum;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        head_merge(m, sum, bi, __shfl_xor(m, o, 64), __shfl_xor(sum, o, 64), __shfl_xor(bi, o, 64));
+    if (__any(nan) && lane == 0) atomicOr(status, STATUS_NAN);
+    if (lane == 0) {
+        tok[c] = bi;
+        conf[c] = 1.0f / sum;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -654,8 +656,17 @@ int dkv_launch_head_stats(hipStream_t s, int cands, const float *logits, const i
     hipLaunchKernelGGL(head_stats_partial_kernel, dim3(HEAD_SLICES, cands), dim3(256), 0, s, logits, counts, V,
                        mask_id, part);
     DKV_LAUNCH_CHECK();
-    hipLaunchKernelGGL(head_stats_final_kernel, dim3((cands + 63) / 64), dim3(64), 0, s, part, counts, tok, conf,
-                       status);
+    hipLaunchKernelGGL(head_stats_final_kernel, dim3((cands + 3) / 4), dim3(256), 0, s, part, HEAD_SLICES, counts, tok,
+                       conf, status);
+    DKV_LAUNCH_CHECK();
+    return DKV_OK;
+}
+
+int dkv_launch_head_merge(hipStream_t s, int cands, const void *head_part, int n_part, const int *counts, int *tok,
+                          float *conf, int *status) {
+    if (cands <= 0) return DKV_OK;
+    hipLaunchKernelGGL(head_stats_final_kernel, dim3((cands + 3) / 4), dim3(256), 0, s,
+                       static_cast<const HeadPartial *>(head_part), n_part, counts, tok, conf, status);
     DKV_LAUNCH_CHECK();
     return DKV_OK;
 }

@@ -30,6 +30,26 @@ def test_cache_variants_teacher_forced(model, variant):
     run_side_by_side(model, run, 7, 8)
 
 
+ODD_BF16 = ModelShape(n_layers=2, d_model=200, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=328,
+                      vocab=520, mask_id=519, dtype=BF16)
+
+
+def test_bf16_model_whose_widths_do_not_fit_the_tile_kernel_takes_the_unfused_path():
+    """d_model = 200 is no multiple of the projections' K tile: register-staged projection kernel, SwiGLU and the
+    vocabulary statistics in launches of their own (fp32 logits written and read back)."""
+    run = RunShape(batch=2, prompt_len=13, gen_len=16, steps=16, block_len=8, refresh_interval=4)
+    run_side_by_side(ODD_BF16, run, 31, 32)
+
+
+def test_block_by_block_and_without_the_debug_copy_of_the_logits():
+    """A small model whose widths fit the tile kernel (SwiGLU and the vocabulary statistics in the projections'
+    epilogues): every block on the device's own inputs, and the head compared on tokens and confidences only, as
+    in a generation, where the logits are never written."""
+    run = RunShape(batch=3, prompt_len=21, gen_len=24, steps=24, block_len=8, refresh_interval=5, variant=DECODE)
+    run_side_by_side(SMALL_BF16, run, 33, 34, per_block=True)
+    run_side_by_side(SMALL_BF16, run, 33, 34, with_logits=False)
+
+
 def test_two_commits_per_step_and_no_delay_ablation():
     run = RunShape(batch=2, prompt_len=10, gen_len=32, steps=16, block_len=16, refresh_interval=4)
     run_side_by_side(SMALL_BF16, run, 9, 10)
