@@ -20,12 +20,18 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes moved per algorithmic byte, per kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# paper_2505_15781_amd/kernel_bench.py at the configs[2] layer shapes (FETCH x2.00, WRITE x1.00 after
-# calibration against a 1 GiB copy kernel); see profiles/projection_cfg2_hbm_traffic_pmc.txt.
-# The counters cannot be read inside this program, so `traffic` scales this run's algorithmic bytes.
+# kernel_bench.py at the configs[2] layer shapes (FETCH x2.00, WRITE x1.00 after calibration against a 1 GiB copy
+# kernel); see profiles/projection_cfg2_hbm_traffic_pmc.txt. Hardware counters cannot be read inside this program,
+# so `roofline.traffic` is null and `roofline.traffic_estimate` scales this run's algorithmic bytes by these ratios.
 MEASURED_TRAFFIC_RATIO = {"gemm_dma<1,1,1,4,4>": 1.03, "gemm_dma<2,1,1,4,4>": 1.09, "gemm_dma<1,3,4,1,4>": 1.12,
                           "gemm_dma<2,3,2,2,3>": 1.12, "gemm_dma<2,2,2,2,3>": 1.33, "gemm_dma<2,4,2,2,3>": 1.44,
                           "gemm_dma<4,4,2,2,2>": 1.12}
+WORKLOADS = {2: "configs[2]: LLaDA-8B shape, dKV-Cache-Decode, batch 1, 256 prompt + 256 generated tokens, 256 steps, "
+                "blocks of 32, refresh every 8 steps",
+             3: "configs[3]: LLaDA-8B shape, dKV-Cache-Greedy (window 4), batch 4, 1024 prompt + 512 generated tokens, "
+                "512 steps, blocks of 64, refresh every 4 steps",
+             4: "configs[4]: Dream-7B shape (GQA 28/4), dKV-Cache-PD, batch 16, 512 prompt + 256 generated tokens, "
+                "256 steps, one block, refresh every 4 steps"}
 
 
 def parse():
@@ -37,7 +43,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn-microbench", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="first run one plain 1 GiB device-to-device copy (reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+                    help="first run one plain 1 GiB copy kernel (reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--no-measured-peaks", action="store_true")
     ap.add_argument("--layers", type=int, default=None, help="debug: truncate the model depth (invalid as a result)")
     return ap.parse_args()
 
@@ -135,6 +142,50 @@ def cpu_baseline(D, model, run, wseed, pseed):
                       f"head in full; {t_body + t_head:.1f}s of CPU work"}
 
 
+def cpu_baseline_small_configs(torch, D, P):
+    """The oracle in full on the two configurations it finishes in seconds, beside the device's time for the same
+    work: configs[0] (tiny fp32 model, whole 32-step generation) and configs[1] (cache update + attention at the five
+    active-set sizes, one call each). Input generation is not counted on either side."""
+    from oracle import sampler as SA
+    from oracle.attn_update import attn_update as oracle_attn_update
+    from paper_2505_15781_amd import binding
+    import numpy as np
+    out = {}
+    model, run, wseed, pseed, _ = D.model_run(0)
+    synth = D.SynthWeights(model, wseed)
+    prompt = D.prompt_tokens(model, run, pseed)
+    synth.embed(); synth.lm_head()
+    for l in range(model.n_layers):
+        synth.layer(l)
+    t0 = time.perf_counter()
+    SA.generate(model, synth, run, prompt)
+    t_cpu = time.perf_counter() - t0
+    g = P.DkvRun(model, run, binding.upload_weights(model, synth), prompt)
+    g.generate()
+    torch.cuda.synchronize()
+    g.reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g.generate()
+    torch.cuda.synchronize()
+    t_gpu = time.perf_counter() - t0
+    g.close()
+    out["configs0"] = {"oracle_tokens_per_s": round(run.gen_len / t_cpu, 2), "oracle_s": round(t_cpu, 4),
+                       "device_tokens_per_s": round(run.gen_len / t_gpu, 1), "device_s": round(t_gpu, 5),
+                       "sample": "the whole 32-step generation"}
+    shape = D.CONFIG1_SHAPE
+    rows = []
+    for i, A in enumerate(D.CONFIG1_ACTIVE_SIZES):
+        c = D.attn_update_case(shape, A, 1100 + i)
+        kc, vc = c["k_cache"].astype(np.float64), c["v_cache"].astype(np.float64)
+        t0 = time.perf_counter()
+        oracle_attn_update(kc, vc, c["q"], c["k_new"], c["v_new"], c["active_idx"], c["active_off"])
+        rows.append({"active": A, "oracle_ms": round((time.perf_counter() - t0) * 1e3, 2)})
+    out["configs1"] = {"calls": rows, "sample": "one cache update + attention call per active-set size, float64; the "
+                                                  "device's time per call is attn_update_configs1[].us"}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -155,7 +206,7 @@ def main():
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        torch.mul(src, 1.0, out=dst)          # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        binding._check(binding.lib.dkv_peak_copy(binding._ptr(src), binding._ptr(dst), 1 << 30, binding._stream()))
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
@@ -206,8 +257,13 @@ def main():
                 "peak": HBM_PEAK_GBS if hbm_bound else MFMA_BF16_PEAK_TFLOPS,
                 "unit": "GB/s" if hbm_bound else "TFLOP/s",
                 "frac": round((gbs / HBM_PEAK_GBS) if hbm_bound else (tfl / MFMA_BF16_PEAK_TFLOPS), 4),
-                "traffic": (round(MEASURED_TRAFFIC_RATIO[dom] * p["bytes"] / p["launches"])
-                            if dom in MEASURED_TRAFFIC_RATIO and args.config == 2 else None),
+                "traffic": None,
+                "traffic_estimate": (round(MEASURED_TRAFFIC_RATIO[dom] * p["bytes"] / p["launches"])
+                                     if dom in MEASURED_TRAFFIC_RATIO and args.config == 2 else None),
+                "traffic_note": "hardware counters are not readable inside this run: traffic_estimate = algorithmic "
+                                "bytes x the FETCH_SIZE/WRITE_SIZE ratio measured for this kernel with rocprofv3 --pmc on "
+                                "kernel_bench.py (profiles/projection_cfg2_hbm_traffic_pmc.txt)",
+                "timing": "HIP events around each launch on the launch stream (includes the gap to the previous kernel)",
                 "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2), "launches": p["launches"],
                 "algorithmic_bytes_per_launch": round(p["bytes"] / p["launches"]),
                 "algorithmic_flops_per_launch": round(p["flops"] / p["launches"])}
@@ -216,20 +272,22 @@ def main():
            "value": round(value, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": f"configs[{args.config}]", "n_layers": model.n_layers, "d_model": model.d_model,
-                      "vocab": model.vocab, "batch": run.batch, "prompt_len": run.prompt_len,
-                      "gen_len": run.gen_len, "denoise_steps": run.steps, "block_len": run.block_len,
-                      "refresh_interval": run.refresh_interval,
-                      "variant": ["decode", "greedy", "prefill", "pd"][run.variant],
+           "config": {"workload": WORKLOADS[args.config] + (f" (truncated to {args.layers} layers: not a result)" if args.layers else ""),
                       "step": "one full generation (all denoising steps)", "host_wall_s": round(t_wall, 3)},
            "roofline": roofline, "kernels": kernels}
     g.close()
     del g, weights
     torch.cuda.empty_cache()
+    if not args.no_measured_peaks:
+        peaks = binding.measured_peaks()
+        out["measured_peaks"] = peaks
+        meas = peaks["hbm_read_GBps"] if roofline["bound"] == "hbm" else peaks["mfma_bf16_TFLOPs"]
+        roofline["frac_of_measured_peak"] = round(roofline["achieved"] / meas, 4)
     if not args.no_attn_microbench:
         out["attn_update_configs1"] = attn_microbench(torch, P, D)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(D, model, run, wseed, pseed)
+        out["cpu_baseline_small_configs"] = cpu_baseline_small_configs(torch, D, P)
     print(json.dumps(out), flush=True)
 
 

@@ -291,6 +291,14 @@ int dkv_gemm_with(const void *x, const void *w, void *y, int32_t m, int32_t n, i
                   int32_t dtype, int32_t kind, int32_t split_k, int32_t options, void *workspace,
                   size_t workspace_bytes, void *stream);
 
+/* Yardsticks for roofline reports, not part of the path: what the chip sustains for a plain copy (the kernel
+ * HBM byte counters are calibrated with), a streaming read, and a register-only dense bf16 MFMA loop. All
+ * (dev) buffers; `bytes` a multiple of 16; sink: at least 2 MiB, never written in practice. dkv_peak_mfma stores
+ * the flops of its launch in *flops (host). The caller times the launches on `stream`. */
+int dkv_peak_copy(const void *src, void *dst, size_t bytes, void *stream);
+int dkv_peak_read(const void *src, void *sink, size_t bytes, void *stream);
+int dkv_peak_mfma(void *sink, int32_t iters, double *flops, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

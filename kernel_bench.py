@@ -6,13 +6,13 @@ over enough weight buffers that every launch streams its weights from HBM. Used 
 kernel timing and under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` for HBM traffic per launch
 (`--copy-calibration` adds one elementwise kernel that reads and writes exactly 1 GiB).
 
-    python -m paper_2505_15781_amd.kernel_bench --config 2 --rows 2,32,64,128,192,256,512
+    python kernel_bench.py --config 2 --rows 2,32,64,128,192,256,512
 """
 import argparse
 import os
 import sys
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))   # runnable as a script from any cwd
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))   # runnable from any cwd
 
 
 def main():
@@ -24,6 +24,9 @@ def main():
     ap.add_argument("--attention", default=None, metavar="ROWS",
                     help="instead: time cache update + attention at the configs[1] shape for these active rows per "
                          "sequence (e.g. 1,8,32,128,512), over rotating caches larger than the last-level cache")
+    ap.add_argument("--peaks", action="store_true",
+                    help="instead: what the chip sustains on the yardstick kernels (cold streaming read, plain copy, "
+                         "register-only bf16 MFMA loop)")
     ap.add_argument("--layout-alternative", action="store_true",
                     help="instead: time the compact-layout concat_reorder operator of the paper's Appendix A per layer-step")
     args = ap.parse_args()
@@ -32,6 +35,17 @@ def main():
     from paper_2505_15781_amd import binding
     from paper_2505_15781_amd.binding import lib, _ptr, _stream, _check
 
+    torch.cuda.set_device(0)
+    if args.copy_calibration:         # peak_copy_kernel: reads exactly 1 GiB and writes exactly 1 GiB
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        _check(lib.dkv_peak_copy(_ptr(src), _ptr(dst), 1 << 30, _stream()))
+        torch.cuda.synchronize()
+        del src, dst
+    if args.peaks:
+        print(binding.measured_peaks(), flush=True)
+        return 0
     if args.layout_alternative:
         return layout_alternative(torch, binding)
     if args.attention:
@@ -41,12 +55,6 @@ def main():
     shapes = {"qkv": (model.qkv_rows, d), "o": (d, model.n_q_heads * model.head_dim), "gate_up": (2 * F, d),
               "down": (d, F)}
     torch.cuda.set_device(0)
-    if args.copy_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.mul(src, 1.0, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
     g = torch.Generator(device="cuda").manual_seed(1)
     for name, (N, K) in shapes.items():
         nbuf = max(2, int(600e6 // (N * K * 2)) + 1)

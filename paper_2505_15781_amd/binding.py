@@ -76,6 +76,9 @@ lib.dkv_attn_update.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp, c_sz, c_vp]
 lib.dkv_attn_update_static.argtypes = [c_vp] * 8 + [c_i32] * 8 + [c_vp]
 STATIC_SCRATCH_BYTES = 4 << 20
 lib.dkv_concat_reorder.argtypes = [c_vp] * 7 + [c_i32] * 6 + [c_vp]
+lib.dkv_peak_copy.argtypes = [c_vp, c_vp, c_sz, c_vp]
+lib.dkv_peak_read.argtypes = [c_vp, c_vp, c_sz, c_vp]
+lib.dkv_peak_mfma.argtypes = [c_vp, c_i32, C.POINTER(C.c_double), c_vp]
 lib.dkv_gemm_workspace_bytes.restype = c_sz
 lib.dkv_gemm_workspace_bytes.argtypes = [c_i32] * 4
 lib.dkv_gemm.argtypes = [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_sz, c_vp]
@@ -346,3 +349,31 @@ def gemm(x, w, dtype, kind=None, split_k=1, options=0):
         _check(lib.dkv_gemm_with(_ptr(x), _ptr(w), _ptr(y), m, n, k, dtype, GEMM_KINDS[kind], split_k, options,
                                  _ptr(ws), nb, _stream()))
     return y
+
+
+def measured_peaks(reps=5):
+    """What this chip sustains on the library's yardstick kernels: cold streaming read and plain copy over 2 GiB
+    buffers (larger than the last-level cache), and a register-only dense bf16 MFMA loop.
+    Returns {"hbm_read_GBps", "hbm_copy_GBps" (read + written bytes), "mfma_bf16_TFLOPs"}."""
+    n = 1 << 31
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1 << 21, dtype=torch.uint8, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    t_read = timed(lambda: _check(lib.dkv_peak_read(_ptr(src), _ptr(sink), n, _stream())))
+    t_copy = timed(lambda: _check(lib.dkv_peak_copy(_ptr(src), _ptr(dst), n, _stream())))
+    flops = C.c_double(0.0)
+    t_mfma = timed(lambda: _check(lib.dkv_peak_mfma(_ptr(sink), 20000, C.byref(flops), _stream())))
+    return {"hbm_read_GBps": round(n / t_read * 1e-9, 1), "hbm_copy_GBps": round(2 * n / t_copy * 1e-9, 1),
+            "mfma_bf16_TFLOPs": round(flops.value / t_mfma * 1e-12, 1)}

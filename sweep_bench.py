@@ -7,14 +7,14 @@ full-width LLaDA-8B-shaped model (random weights: speed only, nothing is checked
 prints generated tokens/s, time per step and the cache ratio (share of the B x L rows per step that are
 reused instead of recomputed, averaged over the steps).
 
-    python -m paper_2505_15781_amd.sweep_bench --layers 4
+    python sweep_bench.py --layers 4
 """
 import argparse
 import os
 import sys
 from dataclasses import replace
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))   # runnable as a script from any cwd
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))   # runnable from any cwd
 
 
 def main():
