@@ -289,6 +289,10 @@ def main():
         out["cpu_baseline"] = cpu_baseline(D, model, run, wseed, pseed)
         out["cpu_baseline_small_configs"] = cpu_baseline_small_configs(torch, D, P)
     print(json.dumps(out), flush=True)
+    # release device objects while the runtime (and a profiler around it, if any) is still fully alive
+    import gc
+    gc.collect()
+    torch.cuda.synchronize()
 
 
 if __name__ == "__main__":

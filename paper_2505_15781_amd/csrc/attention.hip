@@ -99,6 +99,20 @@ __device__ __forceinline__ uint4 load16_nt(const void *p) {
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Work-item order of the bf16 kernels. The `inner` workgroups of a (sequence, kv head) pair (query groups or blocks
+// x key slices) read the same K/V rows, and the hardware sends workgroup i to XCD i mod 8, each with an L2 of its
+// own: consecutive ids would have every XCD fetch the pair's K/V once more (measured: 4.2x the K/V bytes from
+// memory with four query blocks per pair). So pair p lives on XCD p mod 8: its workgroups take the ids
+// p mod 8 + 8 (inner (p / 8) + w), w < inner, which are dispatched within a few ids of each other. The grid is
+// padded to a multiple of 8 pairs; returns false for the padding.
+__device__ __forceinline__ bool attn_item(unsigned id, int pairs, int inner, int &pair, int &within) {
+    const unsigned xcd = id & 7, slot = id >> 3;
+    pair = (int)(slot / inner) * 8 + (int)xcd;
+    within = (int)(slot % inner);
+    return pair < pairs;
+}
+static inline unsigned attn_grid(long pairs, int inner) { return (unsigned)((pairs + 7) / 8 * 8 * inner); }
+
 #include "attn_shared.h"
 #include "attn_ksplit.h"
 
@@ -290,7 +304,7 @@ int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache,
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
     long pairs = (long)rows_upper * n_q_heads;
     if (plan.ksplit_nq) {
-        const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_groups * plan.splits);
+        const unsigned wgs = attn_grid((long)batch * n_kv_heads, plan.q_groups * plan.splits);
 #define KSPLIT_F(D, NQ, NW, F)                                                                                 \
     do {                                                                                                       \
         static std::atomic<bool> lds_ok{false};    /* idempotent call: racing threads only repeat it */       \
@@ -344,7 +358,7 @@ int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache,
         }
     } else if (plan.shared_nq) {
         const size_t smem = 2 * 64 * ((128 * 2 + 16) + (128 * 2 + 32));   // two stages of 64 K rows and 64 V rows
-        const unsigned wgs = (unsigned)((long)batch * n_kv_heads * plan.q_blocks * plan.splits);
+        const unsigned wgs = attn_grid((long)batch * n_kv_heads, plan.q_blocks * plan.splits);
         static std::atomic<bool> lds_ok{false};
         if (!lds_ok.load(std::memory_order_acquire)) {
             DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2, 4>),

@@ -33,12 +33,10 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
     unsigned char *vsm = ksm + SM::K_BYTES;
 
     const int G = Hq / Hkv;
-    long item = blockIdx.x;
-    const int split = (int)(item % splits);   item /= splits;
-    const int qg = (int)(item % q_groups);    item /= q_groups;
-    const int kvh = (int)(item % Hkv);
-    const int b = (int)(item / Hkv);
-    if (b >= batch) return;
+    int pair, within;
+    if (!attn_item(blockIdx.x, batch * Hkv, q_groups * splits, pair, within)) return;
+    const int split = within % splits, qg = within / splits;
+    const int kvh = pair % Hkv, b = pair / Hkv;
 
     const int r0 = row_off[b], nrows = row_off[b + 1] - r0;
     const int nq = nrows * G;                    // query rows of this (sequence, kv head)

@@ -23,12 +23,10 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_shared(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int G = Hq / Hkv;
-    long item = blockIdx.x;
-    const int split = (int)(item % splits); item /= splits;
-    const int qb = (int)(item % q_blocks);  item /= q_blocks;
-    const int kvh = (int)(item % Hkv);
-    const int b = (int)(item / Hkv);
-    if (b >= batch) return;
+    int pair, within;
+    if (!attn_item(blockIdx.x, batch * Hkv, q_blocks * splits, pair, within)) return;
+    const int split = within % splits, qb = within / splits;
+    const int kvh = pair % Hkv, b = pair / Hkv;
 
     const int r0 = row_off[b], nrows = row_off[b + 1] - r0;
     const int nq = nrows * G;

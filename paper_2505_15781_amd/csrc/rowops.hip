@@ -474,24 +474,24 @@ __global__ void fill_u8_kernel(uint8_t *p, uint8_t v, size_t n) {
     if (i < n) p[i] = v;
 }
 
-// k_cache[b][:, p, :] = k_new[r], v likewise (the scatter half of dkv_attn_update)
-template <typename T>
-__global__ __launch_bounds__(256) void scatter_rows_kernel(const T *__restrict__ k_new,
-                                                           const T *__restrict__ v_new,
+// k_cache[b][:, p, :] = k_new[r], v likewise (the scatter half of dkv_attn_update): 16-byte pieces, one per lane;
+// a (row, head) is dh * sizeof(T) contiguous bytes on both sides (cpr pieces)
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4 *__restrict__ k_new,
+                                                           const uint4 *__restrict__ v_new,
                                                            const int *__restrict__ idx,
-                                                           const int *__restrict__ off, T *__restrict__ Kc,
-                                                           T *__restrict__ Vc, int batch, int Hkv, int L,
-                                                           int dh) {
+                                                           const int *__restrict__ off, uint4 *__restrict__ Kc,
+                                                           uint4 *__restrict__ Vc, int batch, int Hkv, int L,
+                                                           int cpr) {
     const int r = blockIdx.x;
     if (r >= off[batch]) return;
     int b = 0;
     while (r >= off[b + 1]) ++b;
     const int p = idx[r];
-    for (int e = threadIdx.x; e < Hkv * dh; e += 256) {
-        const int h = e / dh, i = e % dh;
-        const size_t dst = (((size_t)b * Hkv + h) * L + p) * dh + i;
-        Kc[dst] = k_new[(size_t)r * Hkv * dh + e];
-        Vc[dst] = v_new[(size_t)r * Hkv * dh + e];
+    for (int e = threadIdx.x; e < Hkv * cpr; e += 256) {
+        const int h = e / cpr, i = e % cpr;
+        const size_t dst = (((size_t)b * Hkv + h) * L + p) * cpr + i;
+        Kc[dst] = k_new[(size_t)r * Hkv * cpr + e];
+        Vc[dst] = v_new[(size_t)r * Hkv * cpr + e];
     }
 }
 
@@ -727,12 +727,10 @@ int dkv_launch_scatter_rows(int dtype, hipStream_t s, int rows, const void *k_ne
                             const int *idx, const int *off, void *Kc, void *Vc, int batch, int Hkv, int L,
                             int dh) {
     if (rows <= 0) return DKV_OK;
-    if (dtype == DKV_BF16)
-        hipLaunchKernelGGL((scatter_rows_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, (const bf16_t *)k_new,
-                           (const bf16_t *)v_new, idx, off, (bf16_t *)Kc, (bf16_t *)Vc, batch, Hkv, L, dh);
-    else
-        hipLaunchKernelGGL((scatter_rows_kernel<float>), dim3(rows), dim3(256), 0, s, (const float *)k_new,
-                           (const float *)v_new, idx, off, (float *)Kc, (float *)Vc, batch, Hkv, L, dh);
+    const int row_bytes = dh * (dtype == DKV_BF16 ? 2 : 4);
+    if (row_bytes % 16) { dkv_set_error("a cache row of %d bytes is not a multiple of 16", row_bytes); return DKV_E_UNSUPPORTED; }
+    hipLaunchKernelGGL(scatter_rows_kernel, dim3(rows), dim3(256), 0, s, (const uint4 *)k_new, (const uint4 *)v_new, idx, off,
+                       (uint4 *)Kc, (uint4 *)Vc, batch, Hkv, L, row_bytes / 16);
     DKV_LAUNCH_CHECK();
     return DKV_OK;
 }
