@@ -1,4 +1,3 @@
-#!/usr/bin/env python3
 """Benchmark of the dKV-Cache hot path on one MI355X.
 
 A "step" here is one whole generation of the LLaDA-8B-shaped dKV-Cache-Decode configuration

@@ -38,30 +38,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
     const int split = within % splits, qg = within / splits;
     const int kvh = pair % Hkv, b = pair / Hkv;
 
-    const int r0 = row_off[b], nrows = row_off[b + 1] - r0;
-    const int nq = nrows * G;                    // query rows of this (sequence, kv head)
-    const int m0 = qg * NQ * 16;
-    if (m0 >= nq) return;                        // uniform for the workgroup: no barrier is skipped by part of it
-
     const int qi = lane & 15, g = lane >> 4;
-    bf16x8 qf[NQ][DH / 32];
-#pragma unroll
-    for (int j = 0; j < NQ; ++j) {
-        const int mq = m0 + 16 * j + qi;
-        // rows beyond the host's bound have no slot in the output or partial buffers
-        const bool ok = mq < nq && r0 + mq / G < rows_cap;
-        const bf16_t *qp = Q + ((size_t)(ok ? r0 + mq / G : 0) * Hq + kvh * G + (ok ? mq % G : 0)) * DH + 8 * g;
-#pragma unroll
-        for (int ks = 0; ks < DH / 32; ++ks) {
-            uint4 v = ok ? *reinterpret_cast<const uint4 *>(qp + 32 * ks) : make_uint4(0, 0, 0, 0);
-            qf[j][ks] = *reinterpret_cast<bf16x8 *>(&v);
-        }
-    }
-
     bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
     bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
-    int my_pos = -1;                             // FUSE: active position number `lane` of this sequence
-    if (FUSE && lane < nrows && r0 + lane < rows_cap) my_pos = active_idx[r0 + lane];
     const int n_tiles = (L + KT - 1) / KT;
     const int t_begin = split * tiles_per_split, t_end = min(n_tiles, t_begin + tiles_per_split);
 
@@ -120,8 +99,32 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
     }
 
     // this wavefront's tiles: t_begin + wave, + NW, + 2 NW, ...
+    // The first tile's loads are issued before the row offsets and the query rows are fetched: the K/V addresses do
+    // not depend on them, so the memory latencies overlap instead of adding up (the kernel is latency-bound at small
+    // active sets). A workgroup that turns out to have no query rows has fetched a tile for nothing.
     int t = t_begin + wave;
     if (t < t_end) load_tile(t);
+
+    const int r0 = row_off[b], nrows = row_off[b + 1] - r0;
+    const int nq = nrows * G;                    // query rows of this (sequence, kv head)
+    const int m0 = qg * NQ * 16;
+    if (m0 >= nq) return;                        // uniform for the workgroup: no barrier is skipped by part of it
+    int my_pos = -1;                             // FUSE: active position number `lane` of this sequence
+    if (FUSE && lane < nrows && r0 + lane < rows_cap) my_pos = active_idx[r0 + lane];
+    bf16x8 qf[NQ][DH / 32];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const int mq = m0 + 16 * j + qi;
+        // rows beyond the host's bound have no slot in the output or partial buffers
+        const bool ok = mq < nq && r0 + mq / G < rows_cap;
+        const bf16_t *qp = Q + ((size_t)(ok ? r0 + mq / G : 0) * Hq + kvh * G + (ok ? mq % G : 0)) * DH + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < DH / 32; ++ks) {
+            uint4 v = ok ? *reinterpret_cast<const uint4 *>(qp + 32 * ks) : make_uint4(0, 0, 0, 0);
+            qf[j][ks] = *reinterpret_cast<bf16x8 *>(&v);
+        }
+    }
+
     for (; t < t_end; t += NW) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();

@@ -274,3 +274,50 @@ def test_bad_arguments_are_errors_not_faults():
     with pytest.raises(P.DkvError) as e:
         P.attn_update(kc, kc.clone(), q, kn, kn, idx, off, q.clone(), 1, 1, BF16, None)
     assert e.value.code == -3 and "head_dim" in str(e.value)
+
+
+def test_yardstick_kernels_copy_exactly_and_report_their_flops():
+    """The benchmark's yardsticks: the copy kernel moves every byte (it calibrates the HBM byte counters), the MFMA loop
+    reports the flops of its launch, and the three measured rates are of the chip's order of magnitude."""
+    import ctypes as C
+    from paper_2505_15781_amd import binding as b
+    n = (1 << 20) + 48
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    b._check(b.lib.dkv_peak_copy(b._ptr(src), b._ptr(dst), n, b._stream()))
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    assert b.lib.dkv_peak_copy(b._ptr(src), b._ptr(dst), n - 1, b._stream()) == -1      # not a multiple of 16 bytes
+    sink = torch.zeros(1 << 21, dtype=torch.uint8, device="cuda")
+    flops = C.c_double(0.0)
+    b._check(b.lib.dkv_peak_mfma(b._ptr(sink), 10, C.byref(flops), b._stream()))
+    torch.cuda.synchronize()
+    assert flops.value == 2048 * 4 * 10 * 4 * 2.0 * 32 * 32 * 16 and not sink.any()
+    p = b.measured_peaks(reps=2)
+    assert 1000 < p["hbm_read_GBps"] < 8000 and 1000 < p["hbm_copy_GBps"] < 8000 and 300 < p["mfma_bf16_TFLOPs"] < 2600
+
+
+def test_profile_report_counts_the_bytes_each_projection_really_moves():
+    """dkv_profile_begin / end: per kernel kind launches and algorithmic bytes and flops; gate/up with the fused
+    SwiGLU counts its bf16 [M, N/2] output, the vocabulary projection none (its epilogue keeps statistics only)."""
+    import paper_2505_15781_amd as P
+    from paper_2505_15781_amd import binding
+    from dkv_inputs.configs import ModelShape, RunShape
+    m = ModelShape(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=384, vocab=520, mask_id=519,
+                   dtype=BF16)
+    r = RunShape(batch=2, prompt_len=8, gen_len=8, steps=8, block_len=8, refresh_interval=4)
+    g = P.DkvRun(m, r, binding.random_weights(m, 3), D.prompt_tokens(m, r, 4))
+    g.profile_begin()
+    g.denoise_step(0)
+    prof = g.profile_end()
+    rows, cands, d, F, V = 2 * 16, 2 * 8, m.d_model, m.d_ffn, m.vocab
+    nqkv, qn = m.qkv_rows, m.n_q_heads * m.head_dim
+    proj = lambda M, N, K, out: (M * K + N * K) * 2 + out
+    want_bytes = m.n_layers * (proj(rows, nqkv, d, 4 * rows * nqkv) + proj(rows, d, qn, 4 * rows * d) +
+                               proj(rows, 2 * F, d, 2 * rows * F) + proj(rows, d, F, 4 * rows * d)) + proj(cands, V, d, 0)
+    want_flops = m.n_layers * 2.0 * rows * d * (nqkv + qn + 2 * F + F) + 2.0 * cands * V * d
+    got = [v for k, v in prof.items() if k != "attention" and v["launches"]]
+    assert sum(v["launches"] for v in got) == 4 * m.n_layers + 1
+    assert sum(v["bytes"] for v in got) == want_bytes and sum(v["flops"] for v in got) == want_flops
+    assert prof["attention"]["launches"] == m.n_layers
+    g.close()
