@@ -57,7 +57,7 @@ struct Layout {
     size_t head_part;
     size_t part_floats, attn_part_bytes;
     int rows_cap, cand_cap;
-    int head_tiles_cap;    // most column tiles of the vocabulary projection
+    size_t head_records;   // most (candidate row, column tile) records a vocabulary projection leaves
     bool head_fused;       // softmax statistics leave the vocabulary projection's epilogue: no fp32 logits buffer
 };
 
@@ -78,13 +78,14 @@ Layout make_layout(const dkv_model_desc &m, const dkv_run_desc &r) {
         GemmPlan p4 = dkv_gemm_plan(m.dtype, rows, m.d_model, m.d_ffn);
         size_t a = (size_t)p1.split_k * rows * nqkv, b = (size_t)p2.split_k * rows * m.d_model,
                c = (size_t)p3.split_k * rows * 2 * m.d_ffn, d = (size_t)p4.split_k * rows * m.d_model;
+        if (dkv_gemm_can_fuse_swiglu(m.dtype, 2 * m.d_ffn, m.d_model, p3)) c = 0;   // SwiGLU in the epilogue: no fp32 product
         if (a > pf) pf = a;
         if (b > pf) pf = b;
         if (c > pf) pf = c;
         if (d > pf) pf = d;
     }
     y.head_fused = true;
-    y.head_tiles_cap = 1;
+    y.head_records = 1;
     for (int c = 1; c <= y.cand_cap; ++c) {
         GemmPlan p = dkv_gemm_plan(m.dtype, c, m.vocab, m.d_model);
         if (p.split_k > 1) {
@@ -93,7 +94,7 @@ Layout make_layout(const dkv_model_desc &m, const dkv_run_desc &r) {
         }
         // the epilogue needs the tile kernel with one K slice for every candidate count of the run
         if (!dkv_gemm_can_fuse_head(m.dtype, m.d_model, p)) y.head_fused = false;
-        else if (dkv_gemm_tiles_n(p, m.vocab) > y.head_tiles_cap) y.head_tiles_cap = dkv_gemm_tiles_n(p, m.vocab);
+        else if ((size_t)c * dkv_gemm_tiles_n(p, m.vocab) > y.head_records) y.head_records = (size_t)c * dkv_gemm_tiles_n(p, m.vocab);
     }
     y.part_floats = pf;
     size_t ap = 0;
@@ -132,7 +133,7 @@ Layout make_layout(const dkv_model_desc &m, const dkv_run_desc &r) {
     // fp32 logits of the candidate rows: only when the head's statistics cannot leave the projection's epilogue
     // (a caller who wants the logits passes a buffer of their own)
     y.logits = take(y.head_fused ? 0 : (size_t)y.cand_cap * m.vocab * 4);
-    y.head_part = take(y.head_fused ? (size_t)y.cand_cap * y.head_tiles_cap * sizeof(HeadPartial)
+    y.head_part = take(y.head_fused ? y.head_records * sizeof(HeadPartial)
                                     : dkv_head_stats_scratch_bytes(y.cand_cap));
     y.part = take(y.part_floats * 4);
     y.attn_part = take(y.attn_part_bytes);
