@@ -99,6 +99,12 @@ __device__ __forceinline__ uint4 load16_nt(const void *p) {
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// 16 bytes, plain
+__device__ __forceinline__ uint4 load16(const void *p) {
+    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Work-item order of the bf16 kernels. The `inner` workgroups of a (sequence, kv head) pair (query groups or blocks
 // x key slices) read the same K/V rows, and the hardware sends workgroup i to XCD i mod 8, each with an L2 of its
 // own: consecutive ids would have every XCD fetch the pair's K/V once more (measured: 4.2x the K/V bytes from
@@ -361,19 +367,29 @@ int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache,
         const unsigned wgs = attn_grid((long)batch * n_kv_heads, plan.q_blocks * plan.splits);
         static std::atomic<bool> lds_ok{false};
         if (!lds_ok.load(std::memory_order_acquire)) {
-            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2, 4>),
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2, 4, false>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1, 8>),
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2, 4, true>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1, 8, false>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1, 8, true>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
             lds_ok.store(true, std::memory_order_release);
         }
-#define SHARED(NQ_, NW_)                                                                                          \
-    hipLaunchKernelGGL((attn_bf16_shared<NQ_, NW_>), dim3(wgs), dim3(64 * NW_), smem, stream, (const bf16_t *)q,  \
+#define SHARED(NQ_, NW_, ONCE_)                                                                                   \
+    hipLaunchKernelGGL((attn_bf16_shared<NQ_, NW_, ONCE_>), dim3(wgs), dim3(64 * NW_), smem, stream, (const bf16_t *)q,  \
                        (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out, (float *)partial, \
                        batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits, plan.tiles_per_split,    \
                        rows_upper, scale_log2e)
-        if (plan.shared_waves == 8) SHARED(1, 8);
-        else SHARED(2, 4);
+        const bool once = plan.q_blocks == 1;       // nobody else reads the K/V rows of a workgroup
+        if (plan.shared_waves == 8) {
+            if (once) SHARED(1, 8, true);
+            else SHARED(1, 8, false);
+        } else {
+            if (once) SHARED(2, 4, true);
+            else SHARED(2, 4, false);
+        }
 #undef SHARED
         DKV_LAUNCH_CHECK();
         if (plan.splits > 1) {

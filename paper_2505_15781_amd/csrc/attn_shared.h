@@ -9,8 +9,8 @@
 // from L2 once per 64*NQ query rows instead of once per 16.
 #pragma once
 
-template <int NQ, int NW>
-__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_shared(
+template <int NQ, int NW, bool ONCE>
+__global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_shared(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
     const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
     int Hq, int Hkv, int L, int q_blocks, int splits, int tiles_per_split, int rows_cap,
@@ -59,24 +59,23 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_shared(
     // per thread: CH chunks (16 B) of K and of V per tile, in register set A or B on their way to LDS
     constexpr int NT = 64 * NW, CH = KT2 * (DH / 8) / NT;
     uint4 kA[CH], vA[CH], kB[CH], vB[CH];
-    // With one block of query tiles per (sequence, kv head) nobody else reads these K/V rows in this launch: they
-    // are fetched with the non-temporal hint; with several blocks they are meant to be found in L2 again.
-    const bool read_once = q_blocks == 1;
+    // ONCE: one block of query tiles per (sequence, kv head), so nobody else reads these K/V rows in this launch and
+    // they are fetched with the non-temporal hint; with several blocks they are meant to be found in L2 again.
+    // The loads are unconditional (keys past the end are clamped to the last row: their scores are masked and their
+    // probabilities are zero) so that the code is one straight line and the waits below can count: with a branch
+    // around every load the compiler can only wait for all of them, which puts the loads of the tile after next in
+    // front of the products they are meant to overlap.
     auto load_tile = [&](int t, uint4 (&kr)[CH], uint4 (&vr)[CH]) {
         const int key0 = t * KT2;
-        if (read_once) {
 #pragma unroll
-            for (int i = 0; i < CH; ++i) {
-                const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = key0 + key;
-                kr[i] = gk < L ? load16_nt(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
-                vr[i] = gk < L ? load16_nt(Vb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < CH; ++i) {
-                const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = key0 + key;
-                kr[i] = gk < L ? *reinterpret_cast<const uint4 *>(Kb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
-                vr[i] = gk < L ? *reinterpret_cast<const uint4 *>(Vb + (size_t)gk * DH + ch * 8) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < CH; ++i) {
+            const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = min(key0 + key, L - 1);
+            if (ONCE) {
+                kr[i] = load16_nt(Kb + (size_t)gk * DH + ch * 8);
+                vr[i] = load16_nt(Vb + (size_t)gk * DH + ch * 8);
+            } else {
+                kr[i] = load16(Kb + (size_t)gk * DH + ch * 8);
+                vr[i] = load16(Vb + (size_t)gk * DH + ch * 8);
             }
         }
     };
@@ -138,23 +137,24 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_shared(
     };
 
     // Tile t0 + i is multiplied out of LDS stage i & 1. t0 and t1 are uniform for the workgroup, so every
-    // wavefront passes the same barriers.
-    if (t0 < t1) {
-        load_tile(t0, kA, vA);
-        store_tile(0, kA, vA);
-    }
+    // wavefront passes the same barriers. Prefetches past the slice fetch its last tile again (never stored): every
+    // pass issues the same loads, so the wait in front of a store is for exactly the tile it stores.
+    if (t0 >= t1) return;
+    const int t_last = t1 - 1;
+    load_tile(t0, kA, vA);
+    store_tile(0, kA, vA);
     if (NW == 8) {
         // one workgroup per compute unit: while a tile is multiplied, the next one waits in one register set
         // and the one after it is being fetched into the other (16 registers per set)
-        if (t0 + 1 < t1) load_tile(t0 + 1, kA, vA);
+        load_tile(min(t0 + 1, t_last), kA, vA);
         __syncthreads();
         for (int t = t0; t < t1; t += 2) {
-            if (t + 2 < t1) load_tile(t + 2, kB, vB);
+            load_tile(min(t + 2, t_last), kB, vB);
             multiply(t, 0);
             if (t + 1 < t1) store_tile(1, kA, vA);
             __syncthreads();
             if (t + 1 >= t1) break;
-            if (t + 3 < t1) load_tile(t + 3, kA, vA);
+            load_tile(min(t + 3, t_last), kA, vA);
             multiply(t + 1, 1);
             if (t + 2 < t1) store_tile(0, kB, vB);
             __syncthreads();
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_shared(
         __syncthreads();
         for (int t = t0; t < t1; ++t) {
             const int stage = (t - t0) & 1;
-            if (t + 1 < t1) load_tile(t + 1, kA, vA);
+            load_tile(min(t + 1, t_last), kA, vA);
             multiply(t, stage);
             if (t + 1 < t1) store_tile(stage ^ 1, kA, vA);
             __syncthreads();
