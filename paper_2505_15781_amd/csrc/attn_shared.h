@@ -7,15 +7,21 @@
 // loads of the next tile (with 8 wavefronts: of the next two) are in flight while the current one is multiplied. Each wavefront multiplies its own NQ query
 // tiles against the shared tile, so a K or V fragment read from LDS feeds NQ MFMAs and the tile is read
 // from L2 once per 64*NQ query rows instead of once per 16.
+//
+// FUSE (only for launches with one workgroup per (sequence, kv head): one block of query tiles, one key slice):
+// the cache update of the step (Eq. 4: the rows of M_{t-1} are replaced by the freshly computed ones) happens
+// here instead of in a scatter launch of its own. The workgroup first copies the new rows of its pair into the
+// cache, makes them visible to itself, and then streams the cache as usual; no other workgroup reads those rows.
 #pragma once
 
-template <int NQ, int NW, bool ONCE>
+template <int NQ, int NW, bool ONCE, bool FUSE>
 __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_shared(
-    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
+    const bf16_t *__restrict__ Q, bf16_t *Kc, bf16_t *Vc,
     const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
     int Hq, int Hkv, int L, int q_blocks, int splits, int tiles_per_split, int rows_cap,
-    float scale_log2e) {
-    constexpr int DH = 128, KT2 = 64;
+    float scale_log2e, const bf16_t *__restrict__ k_new, const bf16_t *__restrict__ v_new,
+    const int *__restrict__ active_idx) {
+    constexpr int DH = 128, KT2 = 64, NT = 64 * NW;
     constexpr int K_STRIDE = DH * 2 + 16;      // bytes per key row
     constexpr int V_STRIDE = DH * 2 + 32;      // bytes per V row
     constexpr int K_BYTES = KT2 * K_STRIDE, STAGE_BYTES = K_BYTES + KT2 * V_STRIDE;
@@ -51,13 +57,41 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
         }
     }
 
-    const bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
-    const bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    if (FUSE) {
+        // the new rows of this (sequence, kv head) go into the cache: 16 chunks of K and 16 of V per row, eight
+        // chunks per thread at a time so that their loads are in flight together
+        constexpr int U = 8;
+        for (int c0 = tid; c0 < nrows * 32; c0 += NT * U) {
+            uint4 v[U];
+            int p[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * NT, r = c >> 5, ch = c & 15;
+                const bool is_v = c & 16;
+                p[u] = (c < nrows * 32 && r0 + r < rows_cap) ? active_idx[r0 + r] : -1;
+                const size_t row = ((size_t)(r0 + r) * Hkv + kvh) * DH + ch * 8;
+                v[u] = p[u] >= 0 ? load16((is_v ? v_new : k_new) + row) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * NT, ch = c & 15;
+                const bool is_v = c & 16;
+                if ((unsigned)p[u] < (unsigned)L)                  // positions outside the sequence are ignored
+                    *reinterpret_cast<uint4 *>((is_v ? Vb : Kb) + (size_t)p[u] * DH + ch * 8) = v[u];
+            }
+        }
+        // Workgroup scope is enough: the barrier waits for every wavefront's stores to be acknowledged by L2, and
+        // this unit's L1 (write-through, cleared at kernel start) cannot hold an older copy of rows that nobody has
+        // read yet in this launch. (A device-scope fence here writes back the whole L2: 2x the kernel's time.)
+        __syncthreads();
+    }
     const int n_tiles = (L + KT2 - 1) / KT2;
     const int t0 = split * tiles_per_split, t1 = min(n_tiles, t0 + tiles_per_split);
 
     // per thread: CH chunks (16 B) of K and of V per tile, in register set A or B on their way to LDS
-    constexpr int NT = 64 * NW, CH = KT2 * (DH / 8) / NT;
+    constexpr int CH = KT2 * (DH / 8) / NT;
     uint4 kA[CH], vA[CH], kB[CH], vB[CH];
     // ONCE: one block of query tiles per (sequence, kv head), so nobody else reads these K/V rows in this launch and
     // they are fetched with the non-temporal hint; with several blocks they are meant to be found in L2 again.
@@ -70,12 +104,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = min(key0 + key, L - 1);
+            const bf16_t *ks = Kb + (size_t)gk * DH + ch * 8, *vs = Vb + (size_t)gk * DH + ch * 8;
             if (ONCE) {
-                kr[i] = load16_nt(Kb + (size_t)gk * DH + ch * 8);
-                vr[i] = load16_nt(Vb + (size_t)gk * DH + ch * 8);
+                kr[i] = load16_nt(ks);
+                vr[i] = load16_nt(vs);
             } else {
-                kr[i] = load16(Kb + (size_t)gk * DH + ch * 8);
-                vr[i] = load16(Vb + (size_t)gk * DH + ch * 8);
+                kr[i] = load16(ks);
+                vr[i] = load16(vs);
             }
         }
     };
@@ -137,37 +172,53 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
     };
 
     // Tile t0 + i is multiplied out of LDS stage i & 1. t0 and t1 are uniform for the workgroup, so every
-    // wavefront passes the same barriers. Prefetches past the slice fetch its last tile again (never stored): every
-    // pass issues the same loads, so the wait in front of a store is for exactly the tile it stores.
-    if (t0 >= t1) return;
-    const int t_last = t1 - 1;
-    load_tile(t0, kA, vA);
-    store_tile(0, kA, vA);
-    if (NW == 8) {
-        // one workgroup per compute unit: while a tile is multiplied, the next one waits in one register set
-        // and the one after it is being fetched into the other (16 registers per set)
-        load_tile(min(t0 + 1, t_last), kA, vA);
-        __syncthreads();
-        for (int t = t0; t < t1; t += 2) {
-            load_tile(min(t + 2, t_last), kB, vB);
+    // wavefront passes the same barriers. The steady-state loops issue the same loads on every pass, without a
+    // branch around them, so the wait in front of a tile store counts exactly that tile's loads (behind a
+    // conditional load the compiler can only wait for everything, which would put the prefetch in front of the
+    // products it is meant to overlap); the last tiles, which prefetch less, are peeled off.
+    if (t0 < t1) {
+        load_tile(t0, kA, vA);
+        store_tile(0, kA, vA);
+        int t = t0;
+        if (NW == 8) {
+            // one workgroup per compute unit: while a tile is multiplied, the next one waits in one register set
+            // and the one after it is being fetched into the other (16 registers per set)
+            if (t + 1 < t1) load_tile(t + 1, kA, vA);
+            __syncthreads();
+            for (; t + 3 < t1; t += 2) {
+                load_tile(t + 2, kB, vB);
+                multiply(t, 0);
+                store_tile(1, kA, vA);
+                __syncthreads();
+                load_tile(t + 3, kA, vA);
+                multiply(t + 1, 1);
+                store_tile(0, kB, vB);
+                __syncthreads();
+            }
+            // one to three tiles are left: t in stage 0, t + 1 on its way in set A
+            if (t + 2 < t1) load_tile(t + 2, kB, vB);
             multiply(t, 0);
-            if (t + 1 < t1) store_tile(1, kA, vA);
+            if (t + 1 < t1) {
+                store_tile(1, kA, vA);
+                __syncthreads();
+                multiply(t + 1, 1);
+                if (t + 2 < t1) {
+                    store_tile(0, kB, vB);
+                    __syncthreads();
+                    multiply(t + 2, 0);
+                }
+            }
+        } else {
+            // two workgroups per compute unit cover each other's waits: one tile ahead is enough
             __syncthreads();
-            if (t + 1 >= t1) break;
-            load_tile(min(t + 3, t_last), kA, vA);
-            multiply(t + 1, 1);
-            if (t + 2 < t1) store_tile(0, kB, vB);
-            __syncthreads();
-        }
-    } else {
-        // two workgroups per compute unit cover each other's waits: one tile ahead is enough
-        __syncthreads();
-        for (int t = t0; t < t1; ++t) {
-            const int stage = (t - t0) & 1;
-            load_tile(min(t + 1, t_last), kA, vA);
-            multiply(t, stage);
-            if (t + 1 < t1) store_tile(stage ^ 1, kA, vA);
-            __syncthreads();
+            for (; t + 1 < t1; ++t) {
+                const int stage = (t - t0) & 1;
+                load_tile(t + 1, kA, vA);
+                multiply(t, stage);
+                store_tile(stage ^ 1, kA, vA);
+                __syncthreads();
+            }
+            multiply(t, (t - t0) & 1);
         }
     }
 
@@ -197,4 +248,5 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
             for (int mt = 0; mt < DH / 16; ++mt) *reinterpret_cast<f32x4 *>(rec + 4 + 16 * mt + 4 * g) = acc[j][mt];
         }
     }
+
 }
