@@ -289,18 +289,15 @@ size_t dkv_attn_partial_bytes(const AttnPlan &p, int batch, int n_q_heads, int n
 }
 
 int dkv_attn_can_fuse_update(const AttnPlan &plan, int max_rows_per_seq) {
-    if (!plan.use_mfma) return 0;
-    if (plan.ksplit_nq > 0) return max_rows_per_seq <= 64;      // one lane per active row of the sequence
-    // shared-tile kernel: when one workgroup is the only reader of its pair's K/V rows it replaces them itself
-    return plan.shared_nq > 0 && plan.q_blocks == 1 && plan.splits == 1;
+    return plan.use_mfma && plan.ksplit_nq > 0 && max_rows_per_seq <= 64;
 }
 
 int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache, const int *row_off, void *out,
                          int batch, int n_q_heads, int n_kv_heads, int seq_len, int head_dim, int rows_upper,
                          AttnPlan plan, void *partial, AttnFusedUpdate fuse, hipStream_t stream) {
     if (rows_upper <= 0) return DKV_OK;
-    if (fuse.k_new && !plan.ksplit_nq && !(plan.shared_nq && plan.q_blocks == 1 && plan.splits == 1)) {
-        dkv_set_error("the cache update cannot be fused into this attention launch");
+    if (fuse.k_new && !plan.ksplit_nq) {
+        dkv_set_error("the cache update can only be fused into the key-split attention kernel");
         return DKV_E_INVALID_ARG;
     }
     if (!plan.use_mfma) {
@@ -370,30 +367,28 @@ int dkv_launch_attention(int dtype, const void *q, void *k_cache, void *v_cache,
         const unsigned wgs = attn_grid((long)batch * n_kv_heads, plan.q_blocks * plan.splits);
         static std::atomic<bool> lds_ok{false};
         if (!lds_ok.load(std::memory_order_acquire)) {
-#define SHARED_ATTR(NQ_, NW_, ONCE_, FUSE_)                                                                       \
-    DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<NQ_, NW_, ONCE_, FUSE_>),      \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem))
-            SHARED_ATTR(2, 4, false, false); SHARED_ATTR(2, 4, true, false);
-            SHARED_ATTR(1, 8, false, false); SHARED_ATTR(1, 8, true, false);
-            SHARED_ATTR(2, 4, true, true); SHARED_ATTR(1, 8, true, true);
-#undef SHARED_ATTR
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2, 4, false>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<2, 4, true>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1, 8, false>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            DKV_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_shared<1, 8, true>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
             lds_ok.store(true, std::memory_order_release);
         }
-#define SHARED(NQ_, NW_, ONCE_, FUSE_)                                                                            \
-    hipLaunchKernelGGL((attn_bf16_shared<NQ_, NW_, ONCE_, FUSE_>), dim3(wgs), dim3(64 * NW_), smem, stream,         \
-                       (const bf16_t *)q, (bf16_t *)k_cache, (bf16_t *)v_cache, row_off, (bf16_t *)out,             \
-                       (float *)partial, batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits,         \
-                       plan.tiles_per_split, rows_upper, scale_log2e, (const bf16_t *)fuse.k_new,                   \
-                       (const bf16_t *)fuse.v_new, fuse.active_idx)
+#define SHARED(NQ_, NW_, ONCE_)                                                                                   \
+    hipLaunchKernelGGL((attn_bf16_shared<NQ_, NW_, ONCE_>), dim3(wgs), dim3(64 * NW_), smem, stream, (const bf16_t *)q,  \
+                       (const bf16_t *)k_cache, (const bf16_t *)v_cache, row_off, (bf16_t *)out, (float *)partial, \
+                       batch, n_q_heads, n_kv_heads, seq_len, plan.q_blocks, plan.splits, plan.tiles_per_split,    \
+                       rows_upper, scale_log2e)
         const bool once = plan.q_blocks == 1;       // nobody else reads the K/V rows of a workgroup
         if (plan.shared_waves == 8) {
-            if (fuse.k_new) SHARED(1, 8, true, true);
-            else if (once) SHARED(1, 8, true, false);
-            else SHARED(1, 8, false, false);
+            if (once) SHARED(1, 8, true);
+            else SHARED(1, 8, false);
         } else {
-            if (fuse.k_new) SHARED(2, 4, true, true);
-            else if (once) SHARED(2, 4, true, false);
-            else SHARED(2, 4, false, false);
+            if (once) SHARED(2, 4, true);
+            else SHARED(2, 4, false);
         }
 #undef SHARED
         DKV_LAUNCH_CHECK();

@@ -7,21 +7,15 @@
 // loads of the next tile (with 8 wavefronts: of the next two) are in flight while the current one is multiplied. Each wavefront multiplies its own NQ query
 // tiles against the shared tile, so a K or V fragment read from LDS feeds NQ MFMAs and the tile is read
 // from L2 once per 64*NQ query rows instead of once per 16.
-//
-// FUSE (only for launches with one workgroup per (sequence, kv head): one block of query tiles, one key slice):
-// the cache update of the step (Eq. 4: the rows of M_{t-1} are replaced by the freshly computed ones) happens
-// here instead of in a scatter launch of its own. The workgroup first copies the new rows of its pair into the
-// cache, makes them visible to itself, and then streams the cache as usual; no other workgroup reads those rows.
 #pragma once
 
-template <int NQ, int NW, bool ONCE, bool FUSE>
+template <int NQ, int NW, bool ONCE>
 __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_shared(
-    const bf16_t *__restrict__ Q, bf16_t *Kc, bf16_t *Vc,
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc,
     const int *__restrict__ row_off, bf16_t *__restrict__ out, float *__restrict__ part, int batch,
     int Hq, int Hkv, int L, int q_blocks, int splits, int tiles_per_split, int rows_cap,
-    float scale_log2e, const bf16_t *__restrict__ k_new, const bf16_t *__restrict__ v_new,
-    const int *__restrict__ active_idx) {
-    constexpr int DH = 128, KT2 = 64, NT = 64 * NW;
+    float scale_log2e) {
+    constexpr int DH = 128, KT2 = 64;
     constexpr int K_STRIDE = DH * 2 + 16;      // bytes per key row
     constexpr int V_STRIDE = DH * 2 + 32;      // bytes per V row
     constexpr int K_BYTES = KT2 * K_STRIDE, STAGE_BYTES = K_BYTES + KT2 * V_STRIDE;
@@ -57,41 +51,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
         }
     }
 
-    bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
-    bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
-    if (FUSE) {
-        // the new rows of this (sequence, kv head) go into the cache: 16 chunks of K and 16 of V per row, eight
-        // chunks per thread at a time so that their loads are in flight together
-        constexpr int U = 8;
-        for (int c0 = tid; c0 < nrows * 32; c0 += NT * U) {
-            uint4 v[U];
-            int p[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = c0 + u * NT, r = c >> 5, ch = c & 15;
-                const bool is_v = c & 16;
-                p[u] = (c < nrows * 32 && r0 + r < rows_cap) ? active_idx[r0 + r] : -1;
-                const size_t row = ((size_t)(r0 + r) * Hkv + kvh) * DH + ch * 8;
-                v[u] = p[u] >= 0 ? load16((is_v ? v_new : k_new) + row) : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = c0 + u * NT, ch = c & 15;
-                const bool is_v = c & 16;
-                if ((unsigned)p[u] < (unsigned)L)                  // positions outside the sequence are ignored
-                    *reinterpret_cast<uint4 *>((is_v ? Vb : Kb) + (size_t)p[u] * DH + ch * 8) = v[u];
-            }
-        }
-        // Workgroup scope is enough: the barrier waits for every wavefront's stores to be acknowledged by L2, and
-        // this unit's L1 (write-through, cleared at kernel start) cannot hold an older copy of rows that nobody has
-        // read yet in this launch. (A device-scope fence here writes back the whole L2: 2x the kernel's time.)
-        __syncthreads();
-    }
+    const bf16_t *Kb = Kc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
+    const bf16_t *Vb = Vc + ((size_t)b * Hkv + kvh) * (size_t)L * DH;
     const int n_tiles = (L + KT2 - 1) / KT2;
     const int t0 = split * tiles_per_split, t1 = min(n_tiles, t0 + tiles_per_split);
 
     // per thread: CH chunks (16 B) of K and of V per tile, in register set A or B on their way to LDS
-    constexpr int CH = KT2 * (DH / 8) / NT;
+    constexpr int NT = 64 * NW, CH = KT2 * (DH / 8) / NT;
     uint4 kA[CH], vA[CH], kB[CH], vB[CH];
     // ONCE: one block of query tiles per (sequence, kv head), so nobody else reads these K/V rows in this launch and
     // they are fetched with the non-temporal hint; with several blocks they are meant to be found in L2 again.
@@ -104,13 +70,12 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int c = tid + NT * i, key = c >> 4, ch = c & 15, gk = min(key0 + key, L - 1);
-            const bf16_t *ks = Kb + (size_t)gk * DH + ch * 8, *vs = Vb + (size_t)gk * DH + ch * 8;
             if (ONCE) {
-                kr[i] = load16_nt(ks);
-                vr[i] = load16_nt(vs);
+                kr[i] = load16_nt(Kb + (size_t)gk * DH + ch * 8);
+                vr[i] = load16_nt(Vb + (size_t)gk * DH + ch * 8);
             } else {
-                kr[i] = load16(ks);
-                vr[i] = load16(vs);
+                kr[i] = load16(Kb + (size_t)gk * DH + ch * 8);
+                vr[i] = load16(Vb + (size_t)gk * DH + ch * 8);
             }
         }
     };
@@ -248,5 +213,4 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
             for (int mt = 0; mt < DH / 16; ++mt) *reinterpret_cast<f32x4 *>(rec + 4 + 16 * mt + 4 * g) = acc[j][mt];
         }
     }
-
 }

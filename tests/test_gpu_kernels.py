@@ -194,9 +194,8 @@ def test_attention_shared_tiles_eight_wavefronts(seq_len):
 
 def test_attention_shared_tiles_with_ragged_sequences():
     """Shared-tile kernel over sequences with no active row at all, with every position active (first and last
-    included) and with a few: in its 8-wavefront form with one block of query tiles per (sequence, kv head), where
-    the workgroup replaces the cache rows itself before it streams them, and in its 4-wavefront form with several
-    blocks per pair, where the scatter launch runs first."""
+    included) and with a few: in its 8-wavefront form (one block of query tiles per (sequence, kv head), K/V
+    fetched with the streaming hint) and in its 4-wavefront form (several blocks per pair)."""
     shape = D.AttnUpdateShape(batch=4, n_q_heads=64, n_kv_heads=64, seq_len=300, head_dim=128, dtype=BF16)
     _attn_case(shape, None, 52, ragged=[100, 0, 128, 5])
     shape = D.AttnUpdateShape(batch=4, n_q_heads=128, n_kv_heads=16, seq_len=300, head_dim=128, dtype=BF16)
