@@ -158,15 +158,17 @@ __global__ __launch_bounds__(NT) void residual_norm_kernel(const float *__restri
     __shared__ float red[16];
     const int r = blockIdx.x;
     if (r >= counts[0]) return;
-    float4 v[V4];
+    float4 v[V4], g[V4];
     float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
         const int c = (threadIdx.x + NT * i) * 4;
         float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        g[i] = x;
         if (c < d) {
             const size_t at = (size_t)r * d + c;
             x = *reinterpret_cast<const float4 *>(h + at);
+            g[i] = *reinterpret_cast<const float4 *>(gain + c);      // fetched with the row, not after the reduction
 #pragma unroll 4
             for (int s = 0; s < splits; ++s) x = add4(x, *reinterpret_cast<const float4 *>(part + s * split_stride + at));
         }
@@ -181,8 +183,8 @@ __global__ __launch_bounds__(NT) void residual_norm_kernel(const float *__restri
         if (c < d) {
             const size_t at = (size_t)r * d + c;
             *reinterpret_cast<float4 *>(h + at) = v[i];
-            const float4 g = *reinterpret_cast<const float4 *>(gain + c);
-            store4(a + at, make_float4(v[i].x * rs * g.x, v[i].y * rs * g.y, v[i].z * rs * g.z, v[i].w * rs * g.w));
+            store4(a + at, make_float4(v[i].x * rs * g[i].x, v[i].y * rs * g[i].y, v[i].z * rs * g[i].z,
+                                       v[i].w * rs * g[i].w));
         }
     }
 }
