@@ -205,22 +205,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma(const bf16_t *__restric
   }
 }
 
-struct KindInfo {
-    int bm, bn;
-};
-constexpr KindInfo kKinds[] = {
-    {32, 128},    // GEMM_DMA_32x128   <1,1,1,4> 4 stages
-    {64, 128},    // GEMM_DMA_64x128   <2,1,1,4> 4 stages
-    {128, 128},   // GEMM_DMA_128x128  <2,2,2,2> 3 stages
-    {128, 256},   // GEMM_DMA_128x256  <2,4,2,2> 3 stages
-    {256, 256},   // GEMM_DMA_256x256  <4,4,2,2> 2 stages
-    {128, 96},    // GEMM_DMA_128x96   <1,3,4,1> 4 stages
-    {128, 192},   // GEMM_DMA_128x192  <2,3,2,2> 3 stages
-    {256, 192},   // GEMM_DMA_256x192  <4,3,2,2> 2 stages
-};
-static_assert(sizeof(kKinds) / sizeof(kKinds[0]) == GEMM_DMA_256x192 + 1, "one entry per gemm_dma kind");
-
-
 template <int EPI, int MT, int NT, int WM, int WN, int STAGES>
 int launch_dma(const void *A, const void *W, float *P, int m_upper, int m_cap, const int *m_dev, int n, int k,
                int split, int frac_units, int flags, const GemmEpilogue &ep, hipStream_t s) {
