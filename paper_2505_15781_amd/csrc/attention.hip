@@ -46,12 +46,48 @@ __device__ __forceinline__ bf16x8 vt_operand(const unsigned char *vrow0, int mt,
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Reductions over the four lanes that hold one query (lane, lane ^ 16, lane ^ 32, lane ^ 48), every lane getting the
+// result: gfx950's row swaps (v_permlane16_swap exchanges the odd 16-lane rows of one register with the even rows of
+// another, v_permlane32_swap the upper half of one with the lower half of another; applied to two copies of x they
+// leave "my value" and "my partner's value" side by side). Two vector instructions per stage instead of an LDS
+// round trip (ds_bpermute) with its index arithmetic, on the path between the two products of every key tile.
+__device__ __forceinline__ void swap_rows16(float x, float &u, float &v) {
+    const unsigned a = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    u = __builtin_bit_cast(float, r0);
+    v = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ void swap_rows32(float x, float &u, float &v) {
+    const unsigned a = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    u = __builtin_bit_cast(float, r0);
+    v = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ float query_lanes_max(float x) {
+    float u, v;
+    swap_rows16(x, u, v);
+    x = fmaxf(u, v);
+    swap_rows32(x, u, v);
+    return fmaxf(u, v);
+}
+__device__ __forceinline__ float query_lanes_sum(float x) {
+    float u, v;
+    swap_rows16(x, u, v);
+    x = u + v;
+    swap_rows32(x, u, v);
+    return u + v;
+}
+
 // One online-softmax step of a lane over NT sub-tiles of 16 keys (Eq. 4's softmax, streamed): st[jt][i] is the raw
 // score of key key_base + 16 jt + i against this lane's query. Updates the running max (log2 domain) and sum,
 // rescales the output accumulators, and returns the probabilities as bf16 MFMA operands: operand hh covers
-// sub-tiles 2hh and 2hh+1. The sum uses the unrounded probabilities.
+// sub-tiles 2hh and 2hh+1. The running sum is not formed here: the caller multiplies the same operands with a row of
+// ones (row_sum_operand) into l_acc, so the matrix pipe adds up exactly the rounded probabilities that enter the
+// second product and the vector units are spared sixteen additions per lane and tile; l_acc is only rescaled here.
 template <int NT, int NACC>
-__device__ __forceinline__ void softmax_step(f32x4 (&st)[NT], float &m_run, float &l_run, f32x4 (&acc)[NACC],
+__device__ __forceinline__ void softmax_step(f32x4 (&st)[NT], float &m_run, f32x4 &l_acc, f32x4 (&acc)[NACC],
                                              bf16x8 (&pb)[NT / 2], int key_base, int L, bool masked,
                                              float scale_log2e) {
     if (masked) {              // wave-uniform: only the last tile of a sequence has keys past the end
@@ -66,30 +102,34 @@ __device__ __forceinline__ void softmax_step(f32x4 (&st)[NT], float &m_run, floa
     for (int jt = 0; jt < NT; ++jt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) mx = fmaxf(mx, st[jt][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = query_lanes_max(mx);
     const float m_new = fmaxf(m_run, mx * scale_log2e);
     // Rescale only when some query of the wavefront got a new maximum (rare after the first tiles): for the
     // others the factor would be exactly 1.
     if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        l_run *= alpha;
+        l_acc *= alpha;
 #pragma unroll
         for (int mt = 0; mt < NACC; ++mt) acc[mt] *= alpha;
         m_run = m_new;
     }
-    float psum = 0.f;
 #pragma unroll
     for (int hh = 0; hh < NT / 2; ++hh) {
         f32x8 p;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int e = 0; e < 8; ++e)
             p[e] = __builtin_amdgcn_exp2f(fmaf(st[2 * hh + (e >> 2)][e & 3], scale_log2e, -m_new));
-            psum += p[e];
-        }
         pb[hh] = __builtin_convertvector(p, bf16x8);
     }
-    l_run += psum;
+}
+
+// First operand of the product that sums the probabilities of a query: a 16 x 32 tile whose row 0 is all ones (the
+// lanes with lane % 16 == 0 hold that row). mfma(row_sum_operand, pb, l_acc) adds the sum over the 32 keys of pb to
+// element 0 of l_acc in the lanes below 16 (row 0, column = query); everything else in l_acc stays zero, so the sum
+// over a query's four lanes (query_lanes_sum of element 0) is the running sum.
+__device__ __forceinline__ bf16x8 row_sum_operand(int lane) {
+    const __bf16 one = (lane & 15) == 0 ? (__bf16)1.0f : (__bf16)0.0f;
+    return bf16x8{one, one, one, one, one, one, one, one};
 }
 
 // 16 bytes with the non-temporal hint (data that this launch reads once)

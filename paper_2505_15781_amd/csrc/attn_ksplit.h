@@ -88,12 +88,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
     };
     const unsigned char *vrow0 = vsm + (4 * g + (qi >> 2)) * SM::V_STRIDE + (qi & 3) * 8;
 
-    float m_run[NQ], l_run[NQ];
-    f32x4 acc[NQ][DH / 16];
+    float m_run[NQ];
+    f32x4 acc[NQ][DH / 16], l_acc[NQ];
+    const bf16x8 ones = row_sum_operand(lane);
 #pragma unroll
     for (int j = 0; j < NQ; ++j) {
         m_run[j] = -INFINITY;
-        l_run[j] = 0.f;
+        l_acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < DH / 16; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -168,8 +169,11 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
         bf16x8 pb[NQ][1];
 #pragma unroll
         for (int j = 0; j < NQ; ++j)
-            softmax_step<2, DH / 16>(st[j], m_run[j], l_run[j], acc[j], pb[j], t * KT + 4 * g, L, (t + 1) * KT > L,
+            softmax_step<2, DH / 16>(st[j], m_run[j], l_acc[j], acc[j], pb[j], t * KT + 4 * g, L, (t + 1) * KT > L,
                                      scale_log2e);
+#pragma unroll
+        for (int j = 0; j < NQ; ++j)
+            l_acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[j][0], l_acc[j], 0, 0, 0);
 #pragma unroll
         for (int mt = 0; mt < DH / 16; ++mt) {
             const bf16x8 av = vt_operand(vrow0, mt, SM::V_STRIDE, 0);
@@ -185,9 +189,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_ksplit(
     float *my_rec = reinterpret_cast<float *>(ksm);
 #pragma unroll
     for (int j = 0; j < NQ; ++j) {
-        float l = l_run[j];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
+        const float l = query_lanes_sum(l_acc[j][0]);
         float *rec = my_rec + (j * 16 + qi) * REC;
         if (g == 0) {
             rec[0] = m_run[j];

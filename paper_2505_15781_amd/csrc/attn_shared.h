@@ -90,12 +90,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
     };
     const int v_lane_off = (4 * g + (qi >> 2)) * V_STRIDE + (qi & 3) * 8;
 
-    float m_run[NQ], l_run[NQ];
-    f32x4 acc[NQ][DH / 16];
+    float m_run[NQ];
+    f32x4 acc[NQ][DH / 16], l_acc[NQ];
+    const bf16x8 ones = row_sum_operand(lane);
 #pragma unroll
     for (int j = 0; j < NQ; ++j) {
         m_run[j] = -INFINITY;
-        l_run[j] = 0.f;
+        l_acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < DH / 16; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -123,8 +124,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
         bf16x8 pb[NQ][2];
 #pragma unroll
         for (int j = 0; j < NQ; ++j)
-            softmax_step<4, DH / 16>(st[j], m_run[j], l_run[j], acc[j], pb[j], t * KT2 + 4 * g, L, (t + 1) * KT2 > L,
+            softmax_step<4, DH / 16>(st[j], m_run[j], l_acc[j], acc[j], pb[j], t * KT2 + 4 * g, L, (t + 1) * KT2 > L,
                                      scale_log2e);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int j = 0; j < NQ; ++j)
+                l_acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[j][hh], l_acc[j], 0, 0, 0);
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
@@ -189,9 +195,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) __attribute__((amdgpu_waves_per_eu
 
 #pragma unroll
     for (int j = 0; j < NQ; ++j) {
-        float l = l_run[j];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
+        const float l = query_lanes_sum(l_acc[j][0]);
         if (!q_ok[j]) continue;
         if (splits == 1) {
             const float inv = 1.f / l;
