@@ -208,10 +208,11 @@ int dkv_destroy(dkv_ctx *ctx);
 #define DKV_GEMM_DMA_128x96   5
 #define DKV_GEMM_DMA_128x192  6
 #define DKV_GEMM_DMA_256x192  7
-#define DKV_GEMM_REG_64x128   8   /* bf16 with K not a multiple of 64 */
-#define DKV_GEMM_SIMT         9   /* fp32 mode / generic */
-#define DKV_PROF_ATTN         10  /* attention (including the key-slice merge when it runs) */
-#define DKV_PROF_KINDS        11
+#define DKV_GEMM_DMA_192x256  8
+#define DKV_GEMM_REG_64x128   9   /* bf16 with K not a multiple of 64 */
+#define DKV_GEMM_SIMT         10  /* fp32 mode / generic */
+#define DKV_PROF_ATTN         11  /* attention (including the key-slice merge when it runs) */
+#define DKV_PROF_KINDS        12
 typedef struct {
     int64_t launches;
     double ms, bytes, flops;

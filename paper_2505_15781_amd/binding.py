@@ -65,11 +65,12 @@ class ProfEntry(C.Structure):
 # kernel kinds of the profile report; the tile kernels are named as in a rocprofv3 trace, `*` standing for the epilogue
 # (0 fp32 product, 1 fused SwiGLU, 2 vocabulary statistics), which the report does not tell apart
 PROF_KINDS = ("gemm_dma<*,1,1,1,4,4>", "gemm_dma<*,2,1,1,4,4>", "gemm_dma<*,2,2,2,2,3>", "gemm_dma<*,2,4,2,2,3>",
-              "gemm_dma<*,4,4,2,2,2>", "gemm_dma<*,1,3,4,1,4>", "gemm_dma<*,2,3,2,2,3>", "gemm_dma<*,4,3,2,2,2>", "gemm_reg",
+              "gemm_dma<*,4,4,2,2,2>", "gemm_dma<*,1,3,4,1,4>", "gemm_dma<*,2,3,2,2,3>", "gemm_dma<*,4,3,2,2,2>",
+              "gemm_dma<*,3,4,2,2,2>", "gemm_reg",
               "gemm_simt",
               "attention")
 GEMM_KINDS = {"dma_32x128": 0, "dma_64x128": 1, "dma_128x128": 2, "dma_128x256": 3, "dma_256x256": 4,
-              "dma_128x96": 5, "dma_128x192": 6, "dma_256x192": 7, "reg_64x128": 8, "simt": 9}
+              "dma_128x96": 5, "dma_128x192": 6, "dma_256x192": 7, "dma_192x256": 8, "reg_64x128": 9, "simt": 10}
 lib.dkv_profile_begin.argtypes = [c_vp]
 lib.dkv_profile_end.argtypes = [c_vp, C.POINTER(ProfEntry)]
 lib.dkv_attn_update_workspace_bytes.restype = c_sz

@@ -74,7 +74,8 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Plan of one projection: tile shape and split of the K dimension.
 enum { GEMM_DMA_32x128 = 0, GEMM_DMA_64x128, GEMM_DMA_128x128, GEMM_DMA_128x256, GEMM_DMA_256x256,
-       GEMM_DMA_128x96, GEMM_DMA_128x192, GEMM_DMA_256x192, GEMM_REG_64x128, GEMM_SIMT, GEMM_KINDS };
+       GEMM_DMA_128x96, GEMM_DMA_128x192, GEMM_DMA_256x192, GEMM_DMA_192x256, GEMM_REG_64x128, GEMM_SIMT, GEMM_KINDS };
+enum { GEMM_DMA_LAST = GEMM_DMA_192x256 };      // the gemm_dma tile kernels are the kinds 0 .. GEMM_DMA_LAST
 enum { GEMM_FLAG_STAGGER = 1, GEMM_FLAG_XCD_GROUP = 2, GEMM_FLAG_SWIGLU = 4, GEMM_FLAG_STREAM_W = 8 };
 struct GemmPlan {
     int kind;      // GEMM_* kernel and tile shape

@@ -159,8 +159,12 @@ constexpr KindInfo kKinds[] = {
     {128, 96},    // GEMM_DMA_128x96   <1,3,4,1> 4 stages
     {128, 192},   // GEMM_DMA_128x192  <2,3,2,2> 3 stages
     {256, 192},   // GEMM_DMA_256x192  <4,3,2,2> 2 stages
+    {192, 256},   // GEMM_DMA_192x256  <3,4,2,2> 2 stages
 };
-static_assert(sizeof(kKinds) / sizeof(kKinds[0]) == GEMM_DMA_256x192 + 1, "one entry per gemm_dma kind");
+static_assert(sizeof(kKinds) / sizeof(kKinds[0]) == GEMM_DMA_LAST + 1, "one entry per gemm_dma kind");
+static_assert(GEMM_DMA_192x256 == DKV_GEMM_DMA_192x256 && GEMM_REG_64x128 == DKV_GEMM_REG_64x128 &&
+                  GEMM_SIMT == DKV_GEMM_SIMT && GEMM_KINDS == DKV_PROF_ATTN,
+              "the kinds of the public header are these");
 
 // Number of K slices that is really launched for a requested split (no empty slice).
 int effective_split(int k, int split) {
@@ -202,8 +206,11 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     const int kt_total = k / BK;
     double best = 0.0;
     p.kind = -1;
-    for (int kind = 0; kind <= GEMM_DMA_256x192; ++kind) {
+    for (int kind = 0; kind <= GEMM_DMA_LAST; ++kind) {
         const KindInfo &ki = kKinds[kind];
+        // 192-row tiles are for thousands of rows, where 6144 = 32 x 192 rows against 4096 columns make two full
+        // rounds of workgroups (128x256 tiles: three rounds of smaller tiles; 256x256: one and a half)
+        if (kind == GEMM_DMA_192x256 && m_upper < 4 * ki.bm) continue;
         if (ki.bm > 32 && ki.bm >= 4 * m_upper) continue;       // mostly padding
         if (ki.bm < 128 && m_upper > 4 * ki.bm) continue;       // W re-read too often
         const int tiles = ceil_div(m_upper, ki.bm) * ceil_div(n, ki.bn);
@@ -217,7 +224,9 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
             if (flops / kFlopsPerCu > t_tile) t_tile = flops / kFlopsPerCu;
             const double in_flight = (double)(wgs < 256 ? wgs : 256);
             if (in_flight * fill / kFillAll > t_tile) t_tile = in_flight * fill / kFillAll;
-            double t = rounds * (nk * t_tile + kPipeFill);
+            // (the 192x256 tile's fill and MFMA times are equal, so neither hides behind the other: measured 5 % above
+            // the model where the 256x256 tile meets it)
+            double t = rounds * (nk * t_tile * (kind == GEMM_DMA_192x256 ? 1.05 : 1.0) + kPipeFill);
             const double stream = (2.0 * n * k + 2.0 * m_upper * (double)k + 4.0 * s * m_upper * (double)n) / kStream;
             if (stream > t) t = stream;
             t += kLaunch;
@@ -237,7 +246,7 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
     if (tiles_m == 1) p.flags |= GEMM_FLAG_STAGGER;
     // (not for matrices small enough to stay in the 256 MB last-level cache from one step to the next)
     if (tiles_m == 1 && (size_t)n * k * 2 >= ((size_t)32 << 20)) p.flags |= GEMM_FLAG_STREAM_W;
-    if (((p.kind == GEMM_DMA_256x256 || p.kind == GEMM_DMA_256x192) && tiles_m >= 4) ||
+    if (((p.kind == GEMM_DMA_256x256 || p.kind == GEMM_DMA_256x192 || p.kind == GEMM_DMA_192x256) && tiles_m >= 4) ||
         (p.kind == GEMM_DMA_128x256 && tiles_m >= 6))
         p.flags |= GEMM_FLAG_XCD_GROUP;
     // Giving 256 workgroups 3/4 of a tile's K range each (frac_units, kept for experiments through
@@ -246,7 +255,7 @@ GemmPlan dkv_gemm_plan(int dtype, int m_upper, int n, int k) {
 }
 
 bool dkv_gemm_can_fuse_swiglu(int dtype, int n, int k, const GemmPlan &p) {
-    return dtype == DKV_BF16 && p.kind <= GEMM_DMA_256x192 && p.split_k == 1 && p.frac_units == 0 && (k % BK) == 0 &&
+    return dtype == DKV_BF16 && p.kind <= GEMM_DMA_LAST && p.split_k == 1 && p.frac_units == 0 && (k % BK) == 0 &&
            (n & 1) == 0;
 }
 
@@ -254,7 +263,7 @@ int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p) {
     if (p.split_k < 1 || p.kind < 0 || p.kind >= GEMM_KINDS || p.frac_units < 0) return 0;
     if (p.frac_units) {
         // a 3/4 share: every tile is covered by exactly two workgroups
-        if (p.kind > GEMM_DMA_256x192 || dtype != DKV_BF16 || (k % BK) != 0) return 0;
+        if (p.kind > GEMM_DMA_LAST || dtype != DKV_BF16 || (k % BK) != 0) return 0;
         return p.split_k == 2 && (k / BK) % 4 == 0 && p.frac_units == (k / BK) * 3 / 4;
     }
     if (p.kind == GEMM_SIMT) return p.split_k == 1;
@@ -264,12 +273,12 @@ int dkv_gemm_plan_valid(int dtype, int k, GemmPlan p) {
 }
 
 bool dkv_gemm_can_fuse_head(int dtype, int k, const GemmPlan &p) {
-    return dtype == DKV_BF16 && p.kind >= 0 && p.kind <= GEMM_DMA_256x192 && p.split_k == 1 && p.frac_units == 0 &&
+    return dtype == DKV_BF16 && p.kind >= 0 && p.kind <= GEMM_DMA_LAST && p.split_k == 1 && p.frac_units == 0 &&
            (k % BK) == 0;
 }
 
 int dkv_gemm_tiles_n(const GemmPlan &p, int n) {
-    return p.kind >= 0 && p.kind <= GEMM_DMA_256x192 ? ceil_div(n, kKinds[p.kind].bn) : 0;
+    return p.kind >= 0 && p.kind <= GEMM_DMA_LAST ? ceil_div(n, kKinds[p.kind].bn) : 0;
 }
 
 int dkv_launch_gemm_head(const void *A, const void *W, int m_upper, const int *m_dev, int n, int k, GemmPlan p,
@@ -290,7 +299,7 @@ int dkv_launch_gemm(int dtype, const void *A, const void *W, float *partial, int
         dkv_set_error("projection plan (kind %d, split %d) does not fit dtype %d, K %d", p.kind, p.split_k, dtype, k);
         return DKV_E_UNSUPPORTED;
     }
-    if (p.kind <= GEMM_DMA_256x192) {
+    if (p.kind <= GEMM_DMA_LAST) {
         GemmEpilogue ep;
         if (p.flags & GEMM_FLAG_SWIGLU) {
             if (p.split_k != 1 || p.frac_units) {

@@ -260,6 +260,8 @@ int dispatch_dma(const void *A, const void *W, float *partial, int m_upper, int 
             return launch_dma<EPI, 2, 3, 2, 2, 3>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, ep, stream);
         case GEMM_DMA_256x192:
             return launch_dma<EPI, 4, 3, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, ep, stream);
+        case GEMM_DMA_192x256:
+            return launch_dma<EPI, 3, 4, 2, 2, 2>(A, W, partial, m_upper, m_cap, m_dev, n, k, p.split_k, p.frac_units, p.flags, ep, stream);
     }
     dkv_set_error("kernel %d is not a tile kernel", p.kind);
     return DKV_E_UNSUPPORTED;

@@ -45,6 +45,7 @@ def test_projection_planned_launch_on_a_weight_matrix_that_is_streamed(m):
                                         ("dma_128x128", 4), ("dma_128x256", 2), ("dma_256x256", 1),
                                         ("dma_256x256", 3), ("dma_128x96", 1), ("dma_128x96", 2),
                                         ("dma_128x192", 1), ("dma_128x192", 3), ("dma_256x192", 1), ("dma_256x192", 2),
+                                        ("dma_192x256", 1), ("dma_192x256", 2),
                                         ("reg_64x128", 2)])
 @pytest.mark.parametrize("m,n,k", [(1, 128, 64), (37, 200, 192), (129, 384, 1024), (300, 520, 640), (513, 256, 2048)])
 def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
@@ -63,7 +64,7 @@ def test_every_projection_kernel_on_ragged_shapes(kind, split, m, n, k):
 
 
 @pytest.mark.parametrize("kind", ["dma_32x128", "dma_64x128", "dma_128x128", "dma_128x256", "dma_256x256",
-                                  "dma_128x96", "dma_128x192", "dma_256x192"])
+                                  "dma_128x96", "dma_128x192", "dma_256x192", "dma_192x256"])
 @pytest.mark.parametrize("options", [1, 2, 3, 8, 9])
 @pytest.mark.parametrize("m,n,k,split", [(5, 128, 256, 1), (129, 384, 1024, 1), (300, 520, 768, 2),
                                          (1100, 1536, 512, 1), (1030, 2048, 640, 2)])
@@ -78,7 +79,7 @@ def test_projection_launch_options_leave_the_product_unchanged(kind, options, m,
 
 
 @pytest.mark.parametrize("kind", ["dma_32x128", "dma_64x128", "dma_128x128", "dma_128x256", "dma_256x256",
-                                  "dma_128x96", "dma_128x192", "dma_256x192"])
+                                  "dma_128x96", "dma_128x192", "dma_256x192", "dma_192x256"])
 @pytest.mark.parametrize("m,n,k", [(5, 128, 256), (129, 392, 1024), (300, 520, 768)])
 def test_projection_with_fused_swiglu_epilogue(kind, m, n, k):
     """Rows of w interleave gate_j, up_j; the epilogue writes silu(gate) * up (the feed-forward's activation)
