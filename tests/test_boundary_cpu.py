@@ -78,3 +78,22 @@ def test_projection_and_attention_planners_return_sane_workspace_sizes_without_a
             rows_pad = -(-(-(-rows * g // 16) * 16) // g)
             assert nb <= B * rows_pad * hq * max(1, L // 64) * (dh + 4) * 4, (B, hq, hkv, L, dh, rows, nb)
         assert b.lib.dkv_attn_update_workspace_bytes(B, hq, hkv, L, dh, b.FP32, 8) <= 256     # no partial records
+
+
+def test_kernel_kind_numbers_of_the_header_and_the_binding_agree():
+    """The profile report is indexed by the kind numbers of dkv.h; the binding names them in the same order."""
+    text = open(os.path.join(ROOT, "include", "dkv.h")).read()
+    defs = {m.group(1): int(m.group(2)) for m in re.finditer(r"#define\s+(DKV_(?:GEMM|PROF)_[A-Za-z0-9_]+)\s+(\d+)\b", text)}
+    src = open(os.path.join(ROOT, "paper_2505_15781_amd", "binding.py")).read()
+    kinds = eval(re.search(r"^GEMM_KINDS = (\{.*?\})", src, flags=re.S | re.M).group(1))
+    names = eval(re.search(r"^PROF_KINDS = (\(.*?\))\n", src, flags=re.S | re.M).group(1))
+    assert len(names) == defs["DKV_PROF_KINDS"] and names[defs["DKV_PROF_ATTN"]] == "attention"
+    for name, number in kinds.items():
+        tag = name.upper().replace("X", "x")
+        assert defs["DKV_GEMM_" + tag] == number, name
+    # every projection kind of the header has a name in the binding, and the tile kinds carry their template arguments
+    assert sorted(kinds.values()) == list(range(defs["DKV_PROF_ATTN"]))
+    tiles = {m.group(1): (int(m.group(2)), int(m.group(3))) for m in re.finditer(r"(DKV_GEMM_DMA_(\d+)x(\d+))", text)}
+    for tag, (rows, cols) in tiles.items():
+        mt, nt, wm, wn = (int(x) for x in re.match(r"gemm_dma<\*,(\d),(\d),(\d),(\d),\d>", names[defs[tag]]).groups())
+        assert (32 * mt * wm, 32 * nt * wn) == (rows, cols), tag
